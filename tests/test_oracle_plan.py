@@ -1,0 +1,227 @@
+"""Pins for the duplication-planner oracle (CPU)."""
+import numpy as np
+import pytest
+from scipy.sparse import csr_matrix
+from scipy.sparse.csgraph import maximum_flow
+
+from conftest import read_golden
+from oracle import plan_duplicates, home_slot, route_topk, histogram
+from oracle.alg1_literal import alg1_literal
+from oracle.brute_force import optimal_makespan, best_split_makespan
+from paper_2506_07366_amd import workloads as wl
+
+
+def check_invariants(plan, n_hat, E, G, S, c_max):
+    se = plan.slot_expert.reshape(G, S)
+    q = plan.slot_quota.reshape(G, S)
+    # replica loads sum to expert loads
+    for e in range(E):
+        assert q[se == e].sum() == n_hat[e]
+        assert 1 <= (se == e).sum() <= c_max
+        # at most one copy per rank, and the home slot is kept
+        assert all((se[g] == e).sum() <= 1 for g in range(G))
+        h = home_slot(e, E, G, S)
+        assert plan.slot_expert[h] == e
+    assert np.all(q[se < 0] == 0) and np.all(q >= 0)
+    assert np.array_equal(plan.rank_load_pred, q.sum(axis=1))
+    assert plan.rank_load_pred.sum() == sum(n_hat)
+
+
+def test_fig2_trace():
+    g = read_golden("alg1_fig2_trace.txt")
+    E, G, S, c_max = g["E"][0], g["G"][0], g["S"][0], g["c_max"][0]
+    plan = plan_duplicates(1, g["n_hat"], E, G, S, c_max)
+    assert plan.n_iters == g["n_iters"][0]
+    assert list(plan.rank_load_pred) == g["rank_load"]
+    assert list(plan.slot_expert) == g["slot_expert"]
+    assert list(plan.slot_quota) == g["slot_quota"]
+    se = plan.slot_expert.reshape(G, S)
+    q = plan.slot_quota.reshape(G, S)
+    assert [int(q[r][se[r] == 0].sum()) for r in range(G)] == g["e0_quota_by_rank"]
+    check_invariants(plan, g["n_hat"], E, G, S, c_max)
+
+
+def test_mode0_is_home_placement_and_bottleneck_law():
+    g = read_golden("skewness_fig2.txt")
+    n = g["hist"]
+    plan = plan_duplicates(0, n, 4, 4, 2, 4)
+    assert plan.n_iters == 0
+    assert list(plan.slot_expert) == [0, -1, 1, -1, 2, -1, 3, -1]
+    assert list(plan.slot_quota) == [300, 0, 34, 0, 33, 0, 33, 0]
+    # bottleneck rank load = skewness x average (Background, performance impact)
+    assert plan.rank_load_pred.max() == g["max_rank_load_mode0"][0]
+    assert plan.rank_load_pred.max() == pytest.approx(g["skewness"][0] * sum(n) / 4)
+
+
+def test_home_placement_layout():
+    # E=5, G=3, S=3: H=2 -> ranks host {0,1}, {2,3}, {4}
+    plan = plan_duplicates(0, [1, 2, 3, 4, 5], 5, 3, 3, 3)
+    assert list(plan.slot_expert) == [0, 1, -1, 2, 3, -1, 4, -1, -1]
+    assert list(plan.rank_load_pred) == [3, 7, 5]
+    assert [home_slot(e, 5, 3, 3) for e in range(5)] == [0, 1, 3, 4, 6]
+
+
+def test_uniform_needs_no_iterations():
+    p1 = plan_duplicates(1, [10] * 8, 8, 4, 3, 4)
+    p0 = plan_duplicates(0, [10] * 8, 8, 4, 3, 4)
+    assert p1.n_iters == 0
+    assert np.array_equal(p1.slot_expert, p0.slot_expert)
+    assert np.array_equal(p1.slot_quota, p0.slot_quota)
+
+
+def test_balanced_within_one_with_ample_slots():
+    """'until all GPUs process the same amount of tokens' / loop guard max-min <= 1."""
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        E = int(rng.integers(2, 9))
+        G = int(rng.integers(2, 7))
+        H = -(-E // G)
+        S = H + E                      # room for every expert everywhere
+        n = rng.integers(0, 500, size=E)
+        plan = plan_duplicates(1, n, E, G, S, G)
+        L = plan.rank_load_pred
+        assert L.max() - L.min() <= 1, (E, G, n, L)
+        check_invariants(plan, list(n), E, G, S, G)
+        assert plan.n_iters < 16 * G * S
+
+
+def test_constraints_respected_and_never_worse_than_home():
+    rng = np.random.default_rng(11)
+    for trial in range(60):
+        E = int(rng.integers(2, 13))
+        G = int(rng.integers(2, 7))
+        H = -(-E // G)
+        S = H + int(rng.integers(0, 3))
+        c_max = int(rng.integers(1, G + 1))
+        n = (rng.dirichlet(np.full(E, 0.3)) * 2000).astype(np.int64)
+        p0 = plan_duplicates(0, n, E, G, S, c_max)
+        p1 = plan_duplicates(1, n, E, G, S, c_max)
+        check_invariants(p1, list(n), E, G, S, c_max)
+        assert p1.rank_load_pred.max() <= p0.rank_load_pred.max()
+    # c_max = 1 forbids replicas: tokens can only move between existing hosts -> none
+    p = plan_duplicates(1, [90, 5, 5], 3, 3, 2, 1)
+    assert p.n_iters == 0 and list(p.rank_load_pred) == [90, 5, 5]
+
+
+def test_count_based_equals_literal_per_token_algorithm():
+    rng = np.random.default_rng(2)
+    checked = 0
+    for trial in range(60):
+        E = int(rng.integers(2, 7))
+        G = int(rng.integers(2, 5))
+        H = -(-E // G)
+        S = H + int(rng.integers(0, 3))
+        c_max = int(rng.integers(1, G + 1))
+        T = int(rng.integers(5, 90))
+        p = rng.dirichlet(np.full(E, 0.4))
+        f = rng.choice(E, size=T, p=p)
+        n = np.bincount(f, minlength=E)
+        plan = plan_duplicates(1, n, E, G, S, c_max)
+        load, P, d, it = alg1_literal(f, E, G, S, c_max)
+        se = plan.slot_expert.reshape(G, S)
+        q = plan.slot_quota.reshape(G, S)
+        mine = np.zeros((E, G), dtype=np.int64)
+        for g in range(G):
+            for s in range(S):
+                if se[g, s] >= 0:
+                    mine[se[g, s], g] += q[g, s]
+        # equal-count experts on the hot rank can be taken in a different order by
+        # the two forms (slot order vs expert id); only tie-free runs are compared
+        if not _has_expert_tie(f, E, G, S, c_max):
+            assert np.array_equal(mine, load), (E, G, S, c_max, n)
+            assert plan.n_iters == it
+            checked += 1
+    assert checked >= 25
+
+
+def _has_expert_tie(f, E, G, S, c_max):
+    """Replay the literal algorithm and report whether two experts on the hot GPU
+    ever had equal positive token counts."""
+    load_hist = []
+    it = 0
+    while True:
+        load, P, d, n_it = alg1_literal(f, E, G, S, c_max, max_iters=it)
+        L = load.sum(axis=0)
+        g_h = int(np.argmax(L))
+        col = load[:, g_h]
+        pos = col[col > 0]
+        if len(set(pos.tolist())) != len(pos):
+            return True
+        if n_it < it:
+            return False
+        it += 1
+        if it > 200:
+            return False
+
+
+def _flow_feasible(n, hosts, G, M):
+    E = len(n)
+    # nodes: 0 source, 1..E experts, E+1..E+G ranks, E+G+1 sink
+    N = E + G + 2
+    cap = np.zeros((N, N), dtype=np.int32)
+    for e in range(E):
+        cap[0, 1 + e] = n[e]
+        for g in hosts[e]:
+            cap[1 + e, 1 + E + g] = n[e]
+    for g in range(G):
+        cap[1 + E + g, N - 1] = M
+    return maximum_flow(csr_matrix(cap), 0, N - 1).flow_value == sum(n)
+
+
+def test_subset_bound_equals_max_flow():
+    rng = np.random.default_rng(9)
+    for trial in range(30):
+        E, G = int(rng.integers(2, 6)), int(rng.integers(2, 5))
+        n = [int(v) for v in rng.integers(0, 60, size=E)]
+        hosts = [set(rng.choice(G, size=int(rng.integers(1, G + 1)), replace=False).tolist())
+                 for _ in range(E)]
+        m = best_split_makespan(n, hosts, G)
+        if sum(n) == 0:
+            assert m == 0
+            continue
+        assert _flow_feasible(n, hosts, G, m)
+        assert m == 0 or not _flow_feasible(n, hosts, G, m - 1)
+
+
+def test_greedy_vs_exhaustive_optimum():
+    """Greedy makespan can never beat the exhaustive optimum; the ratio is reported."""
+    rng = np.random.default_rng(21)
+    ratios = []
+    for trial in range(25):
+        E = int(rng.integers(2, 6))
+        G = int(rng.integers(2, 5))
+        H = -(-E // G)
+        S = min(3, H + int(rng.integers(0, 2)))
+        if S < H:
+            continue
+        c_max = G
+        n = (rng.dirichlet(np.full(E, 0.5)) * 300).astype(np.int64) + 1
+        opt = optimal_makespan(n, G, S, c_max)
+        greedy = int(plan_duplicates(1, n, E, G, S, c_max).rank_load_pred.max())
+        assert opt >= -(-int(n.sum()) // G)
+        assert greedy >= opt
+        ratios.append(greedy / opt)
+    assert len(ratios) >= 15
+    assert max(ratios) < 1.6           # observed gap stays small on these inputs
+    # the Figure 2 scenario is solved optimally
+    assert optimal_makespan([900, 100, 100, 100], 4, 2, 4) == 300
+
+
+@pytest.mark.parametrize("name", ["cfg1_tiny_f32", "cfg2_mixtral_dist", "cfg3_mixtral_t2e",
+                                  "cfg4_finegrained", "cfg5_prefill_a0.1_m1", "cfg5_prefill_a1_m2",
+                                  "cfg5_prefill_a10_m1", "cfg5_decode_m1"])
+def test_iteration_cap_never_binds_on_the_workloads(name):
+    cfg = wl.CONFIGS[name]
+    idx, _ = route_topk(wl.gen_logits(cfg), cfg.k)
+    h = histogram(idx, cfg.E)
+    if cfg.mode == 2:
+        hp = histogram(wl.gen_pred_idx(cfg, idx), cfg.E)
+    else:
+        hp = wl.gen_pred_hist(cfg, h)
+    plan = plan_duplicates(cfg.mode, hp, cfg.E, cfg.G, cfg.S, cfg.cmax)
+    check_invariants(plan, list(hp), cfg.E, cfg.G, cfg.S, cfg.cmax)
+    assert plan.n_iters < 16 * cfg.G * cfg.S
+    p0 = plan_duplicates(0, hp, cfg.E, cfg.G, cfg.S, cfg.cmax)
+    assert plan.rank_load_pred.max() <= p0.rank_load_pred.max()
+    print(name, "iters", plan.n_iters, "makespan", plan.rank_load_pred.max(), "home", p0.rank_load_pred.max(),
+          "mean", cfg.A / cfg.G)
