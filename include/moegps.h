@@ -1,0 +1,191 @@
+/*
+ * moegps.h -- C ABI of libmoegps: one MoE FFN layer with dynamic expert
+ * duplication (the setting of MoE-GPS, arXiv 2506.07366) on one AMD MI355X.
+ *
+ * The layer is split into the calls of the paper's problem statement: gate
+ * top-k routing, the per-expert token histogram that Distribution-Only
+ * Prediction forecasts (Eq. (1)), the duplication plan (Algorithm 1), the
+ * dispatch/permutation of tokens to replicas, the grouped SwiGLU expert FFN and
+ * the weighted combine.  G expert-parallel ranks with S expert slots each are
+ * emulated as partitions of one GPU; a "segment" is one slot, global id g*S+s.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer unless it is marked "host".  Buffers are
+ *     contiguous, row-major, 16-byte aligned and owned by the caller; the
+ *     library never allocates, frees or keeps device memory.  Scratch space is
+ *     passed in as a workspace whose size comes from a *_workspace_bytes query.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue kernels on it and return; there is no host
+ *     synchronisation inside, results are valid in stream order.
+ *   - Return value: MOE_OK (0) or a negative MOE_ERR_* code.  Arguments are
+ *     checked on the host (scalars and NULL pointers only); on an error nothing
+ *     has been enqueued.  No exception or abort crosses the boundary.
+ *   - dtype: MOE_DTYPE_F32 (float) or MOE_DTYPE_BF16 (bfloat16 storage, fp32
+ *     accumulation).
+ *   - Notation: T tokens, E experts, k experts per token, A = T*k assignments
+ *     (assignment a = t*k + j is token t's j-th expert), d model width, ffn
+ *     expert hidden width, G ranks, S slots per rank, NSEG = G*S.
+ */
+#ifndef MOEGPS_H
+#define MOEGPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK                        0
+#define MOE_ERR_INVALID_ARG         (-1)
+#define MOE_ERR_UNSUPPORTED         (-2)   /* shape or dtype outside what is built */
+#define MOE_ERR_WORKSPACE_TOO_SMALL (-3)
+#define MOE_ERR_HIP                 (-4)   /* a HIP call failed, see moe_last_hip_error */
+
+#define MOE_DTYPE_F32   0
+#define MOE_DTYPE_BF16  1
+
+#define MOE_MODE_NONE          0   /* home placement only (no prediction) */
+#define MOE_MODE_DISTRIBUTION  1   /* Distribution-Only Prediction, Section 3.2.1 */
+#define MOE_MODE_TOKEN         2   /* Token-to-Expert Prediction, Section 3.2.2 */
+
+/* limits of this build */
+#define MOE_MAX_EXPERTS   1024
+#define MOE_MAX_TOPK        16
+#define MOE_MAX_RANKS      256
+#define MOE_MAX_SLOTS       16   /* per rank */
+#define MOE_MAX_SEGMENTS  2048   /* G*S */
+
+/* Text for a return code (host pointer to a static string). */
+const char* moe_strerror(int code);
+/* The hipError_t (as int) recorded by the last call that returned MOE_ERR_HIP on this thread. */
+int moe_last_hip_error(void);
+/* Version of this ABI (increases when a signature changes). */
+int moe_abi_version(void);
+
+/*
+ * Gate top-k (Background: each token is routed to its top-K experts; the
+ * token->expert map f of Algorithm 1).
+ *   logits   [T, E] float  in   router logits, given directly (finite values)
+ *   topk_idx [T, k] int32  out  experts ordered by (logit descending, index
+ *                               ascending): equal logits go to the lowest index
+ *   topk_w   [T, k] float  out  softmax over the k selected logits
+ * 1 <= k <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS.  T = 0 is a no-op.
+ */
+int moe_route_topk(const float* logits, int T, int E, int k,
+                   int32_t* topk_idx, float* topk_w, void* stream);
+
+/*
+ * Per-expert count n_e = #{a : idx[a] == e} (the n_i of Eq. (1); p_hat_i = n_i/N).
+ *   idx  [n] int32 in   values in [0, E); values outside are ignored
+ *   hist [E] int32 out  overwritten (not accumulated)
+ */
+int moe_histogram(const int32_t* idx, int64_t n, int E, int32_t* hist, void* stream);
+
+/*
+ * Expert duplication plan (Algorithm 1, count-based).  Starts from the home
+ * placement (expert e on rank e / H, slot e % H, H = ceil(E/G)) with every
+ * predicted token on its home, then repeats: hottest rank g_h, coldest rank
+ * g_c, Delta = ceil((L_h - L_c)/2), hottest expert e* on g_h; replicate e* into
+ * the lowest empty slot of g_c if it is not there, has fewer than c_max copies
+ * and g_c has room; move min(Delta, tokens of e* on g_h) tokens.  If that
+ * candidate is infeasible the next experts of g_h (descending load) and then the
+ * next-coldest ranks are tried; the loop ends when max L - min L <= 1, nothing is
+ * feasible, or after 16*G*S iterations.  All ties go to the lowest index.
+ *   mode            MOE_MODE_NONE stops after the home placement
+ *   hist_pred [E]   int32 in   predicted counts (mode 2: histogram of the
+ *                              predicted ids, computed by the caller with
+ *                              moe_histogram); must be >= 0
+ *   c_max           max copies of one expert (>= 1)
+ *   slot_expert    [G*S] int32 out  expert hosted by each slot, -1 = empty
+ *   slot_quota     [G*S] int32 out  planned rows per slot
+ *   rank_load_pred [G]   int32 out  planned rows per rank
+ *   n_iters        [1]   int32 out  iterations of the loop that moved tokens
+ * Requires ceil(E/G) <= S <= MOE_MAX_SLOTS, G <= MOE_MAX_RANKS.
+ */
+int moe_plan_duplicates(int mode, const int32_t* hist_pred, int E, int G, int S, int c_max,
+                        int32_t* slot_expert, int32_t* slot_quota, int32_t* rank_load_pred,
+                        int32_t* n_iters, void* stream);
+
+/*
+ * Dispatch + permutation (the dispatch d of Algorithm 1; stands where the
+ * all-to-all before the expert FFN is, Background "Routing incurs inter-device
+ * communication").  Every assignment gets a segment:
+ *   mode 0: the home slot of its expert;
+ *   mode 1: replicas of expert e in ascending slot id take contiguous ranges of
+ *           e's assignments (ascending a) with boundaries floor(n_e*Q_r/nhat_e),
+ *           Q_r = cumulative planned quota; nhat_e = 0 -> home slot;
+ *   mode 2: if the true expert is among the token's predicted ids, the
+ *           assignment takes its place (stable rank among predicted assignments
+ *           of e) in the planned quotas; otherwise it falls back to the home slot
+ *           of its true expert.
+ * Then the assignments are sorted stably by segment and rows are copied.
+ *   x          [T, d]  dtype in
+ *   topk_idx   [T, k]  int32 in
+ *   pred_idx   [T, k]  int32 in   mode 2 only (rows hold distinct ids), else NULL
+ *   hist_true  [E]     int32 in   histogram of topk_idx (mode 1)
+ *   hist_pred  [E]     int32 in   the histogram the plan was built from (mode 1)
+ *   slot_expert, slot_quota [G*S] int32 in   the plan
+ *   seg_offsets   [G*S+1] int32 out  first row of each segment, last = A
+ *   row_of_assign [A]     int32 out  row of x_perm that holds assignment a
+ *   assign_of_row [A]     int32 out  inverse permutation
+ *   x_perm        [A, d]  dtype out  x_perm[row] = x[assign_of_row[row] / k]; may be
+ *                                    NULL to skip the row copy
+ *   rank_load     [G]     int32 out  rows served by each rank
+ * d * sizeof(dtype) must be a multiple of 16.  A < 2^31.
+ */
+size_t moe_permute_workspace_bytes(int T, int E, int k, int G, int S);
+int moe_permute(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
+                const int32_t* topk_idx, const int32_t* pred_idx,
+                const int32_t* hist_true, const int32_t* hist_pred,
+                const int32_t* slot_expert, const int32_t* slot_quota,
+                int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                void* x_perm, int32_t* rank_load,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One-off repack of the expert weights into the tile order the FFN kernels
+ * stream (expert weights are static across inputs, Discussion "Expert
+ * duplication's communication overhead"; not part of the per-batch path).
+ *   W1, W3 [E, d, ffn], W2 [E, ffn, d]  dtype in (row-major)
+ *   packed  out, moe_packed_weights_bytes(E, d, ffn, dtype) bytes
+ * For MOE_DTYPE_F32 the packed form is a plain copy.
+ */
+size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype);
+int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,
+                     int E, int d, int ffn, void* packed, void* stream);
+
+/*
+ * Grouped SwiGLU expert FFN (Section 3.4: Mixtral-style FFN with SwiGLU; the
+ * dominant cost of the layer, Background "Performance Impacts").  For every row
+ * r of a segment sigma in [seg_begin, seg_end) with e = slot_expert[sigma]:
+ *     y_perm[r] = ( silu(x_perm[r] W1_e) * (x_perm[r] W3_e) ) W2_e
+ * Rows of other segments are not written.  seg_begin/seg_end select a slot
+ * range, e.g. one rank's [g*S, (g+1)*S), so a rank's share can be timed alone.
+ *   x_perm [A, d] dtype in;  y_perm [A, d] dtype out
+ *   seg_offsets [nseg+1], slot_expert [nseg] int32 in (device; read by the kernels)
+ *   packed  in  weights from moe_pack_weights
+ * bf16: products accumulate in fp32, the hidden activation is rounded to bf16
+ * between the two products, the output is rounded to bf16.
+ * bf16 needs d % 64 == 0 and ffn % 64 == 0; f32 needs d % 4 == 0 and ffn % 4 == 0.
+ */
+size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype);
+int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
+                    const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
+                    int seg_begin, int seg_end, const void* packed,
+                    void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Weighted un-permute (stands where the all-to-all after the FFN is):
+ *     out[t, :] = sum_{j<k} topk_w[t, j] * y_perm[row_of_assign[t*k + j], :]
+ * summed in fp32 with j ascending; bf16 output is rounded once at the end.
+ *   y_perm [A, d] dtype in, row_of_assign [A] int32 in, topk_w [T, k] float in,
+ *   out [T, d] dtype out.  d * sizeof(dtype) must be a multiple of 16.
+ */
+int moe_combine(const void* y_perm, int dtype, int T, int d, int k,
+                const int32_t* row_of_assign, const float* topk_w, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEGPS_H */

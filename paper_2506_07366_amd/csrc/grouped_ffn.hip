@@ -1,0 +1,572 @@
+// Grouped SwiGLU expert FFN (Section 3.4: Mixtral-style FFN with SwiGLU; the
+// dominant cost of the layer per the Background's performance discussion):
+//     y = ( silu(x W1_e) * (x W3_e) ) W2_e      for every row of a segment whose
+//                                               slot hosts expert e.
+//
+// bf16 path: two persistent grouped GEMMs on the MFMA units.
+//   GEMM-1: H[A, ffn]  = swiglu( X[A, d] * [W1|W3]_e )    (gate/up columns interleaved
+//           by 32 in the packed weights, so the SwiGLU happens on the accumulators)
+//   GEMM-2: Y[A, d]    = H[A, ffn] * W2_e
+// Packed weights are stored "column-major" ([N][K], K contiguous), the same shape
+// as the activations, so both operands stream as K-contiguous 16-byte pieces
+// straight from global memory into LDS (global_load_lds_dwordx4) and feed
+// v_mfma_f32_32x32x16_bf16 fragments with one ds_read_b128 each.
+// A device-built table of M-tiles follows the ragged segments; workgroups walk
+// the (M-tile, N-tile) space in an order that keeps the tiles running at the
+// same time on a shared set of weight and activation panels.
+//
+// fp32 path (small reference-precision configs): a plain LDS-tiled FMA kernel.
+#include "common.h"
+#include "block_scan.h"
+#include <stdlib.h>
+
+namespace moegps {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned short bf16_t;  // storage
+
+struct MTile {
+    int row0;    // first row of the tile in x_perm
+    int rows;    // valid rows (<= BM)
+    int expert;  // expert hosted by the segment's slot
+    int seg;
+};
+
+// ---------------------------------------------------------------------------
+// weight packing (one-off, weights are static across inputs)
+// ---------------------------------------------------------------------------
+// out[n][k] = in[k][n] for one expert per blockIdx.z; optional interleave of the
+// output row index: rows of W1 go to (n/32)*64 + n%32, rows of W3 32 further.
+__global__ __launch_bounds__(256) void pack_transpose_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
+                                                              int K, int N, size_t in_expert_stride,
+                                                              size_t out_expert_stride, int interleave, int sel) {
+    __shared__ bf16_t tile[32][33];
+    const bf16_t* src = in + (size_t)blockIdx.z * in_expert_stride;
+    bf16_t* dst = out + (size_t)blockIdx.z * out_expert_stride;
+    const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int r = ty; r < 32; r += 8) {
+        const int kk = k0 + r, nn = n0 + tx;
+        tile[r][tx] = (kk < K && nn < N) ? src[(size_t)kk * N + nn] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int nn = n0 + r, kk = k0 + tx;
+        if (nn < N && kk < K) {
+            const int orow = interleave ? ((nn / 32) * 64 + sel * 32 + (nn % 32)) : nn;
+            dst[(size_t)orow * K + kk] = tile[tx][r];
+        }
+    }
+}
+
+__global__ void copy_u4_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = in[i];
+}
+
+// ---------------------------------------------------------------------------
+// M-tile table from the ragged segments
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __restrict__ seg_offsets,
+                                                             const int32_t* __restrict__ slot_expert, int seg_begin,
+                                                             int seg_end, int E, int BM, MTile* __restrict__ tiles,
+                                                             int capacity, int32_t* __restrict__ n_tiles) {
+    __shared__ int cnt[MOE_MAX_SEGMENTS + 1];
+    __shared__ int wave_sum[16];
+    const int ns = seg_end - seg_begin;
+    for (int i = threadIdx.x; i < ns; i += blockDim.x) {
+        const int s = seg_begin + i;
+        const int rows = seg_offsets[s + 1] - seg_offsets[s];
+        const int e = slot_expert[s];
+        cnt[i] = (rows > 0 && e >= 0 && e < E) ? (rows + BM - 1) / BM : 0;
+    }
+    __syncthreads();
+    block_exclusive_scan_2048(cnt, ns, wave_sum);
+    for (int i = threadIdx.x; i < ns; i += blockDim.x) {
+        const int s = seg_begin + i;
+        const int lo = seg_offsets[s], hi = seg_offsets[s + 1];
+        const int nt = cnt[i + 1] - cnt[i];
+        for (int t = 0; t < nt; ++t) {
+            const int slot = cnt[i] + t;
+            if (slot < capacity) {
+                MTile mt;
+                mt.row0 = lo + t * BM;
+                mt.rows = (hi - mt.row0) < BM ? (hi - mt.row0) : BM;
+                mt.expert = slot_expert[s];
+                mt.seg = s;
+                tiles[slot] = mt;
+            }
+        }
+    }
+    if (threadIdx.x == 0) n_tiles[0] = cnt[ns] < capacity ? cnt[ns] : capacity;
+}
+
+// ---------------------------------------------------------------------------
+// bf16 grouped GEMM on MFMA
+// ---------------------------------------------------------------------------
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | (0x7 << 4) | (0xf << 8) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+// 16-byte piece `slot` of LDS row `row` holds global piece slot ^ swz(row): spreads
+// the 32 rows one fragment read touches over all banks
+template <int CPR>
+__device__ __forceinline__ int swz(int row) {
+    if (CPR == 8) return row & 7;
+    if (CPR == 4) return (row >> 1) & 3;
+    return 0;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
+__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
+    const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
+    const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
+    bf16_t* __restrict__ C, int ldc,                 // output [rows, SWIGLU ? N/2 : N]
+    const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int N, int K, int group_n) {
+    constexpr int NW = WGM * WGN;
+    constexpr int NT = NW * 64;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int CPR = BK / 8;                 // 16-byte pieces per tile row
+    constexpr int IA = BM * CPR / 64;           // wave-wide load instructions per A tile
+    constexpr int IB = BN * CPR / 64;
+    constexpr int IAW = IA / NW, IBW = IB / NW;  // per wavefront
+    constexpr int LPT = IAW + IBW;              // loads per thread per k-tile
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    static_assert(IA % NW == 0 && IB % NW == 0, "tile loads must divide over the wavefronts");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA tiles");
+    static_assert(!SWIGLU || (WTN % 64 == 0), "gate/up pairs must sit in one wavefront");
+    static_assert(LPT * (NSTAGE - 1) < 64, "vmcnt range");
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int n_mtiles = n_mtiles_ptr[0];
+    const int n_ntiles = (N + BN - 1) / BN;
+    const int total = n_mtiles * n_ntiles;
+    const int KT = K / BK;
+
+    for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        // (M-tile, N-tile) of this tile id: N-tiles in groups of group_n, M fastest
+        // inside a group, so concurrently running tiles share weight panels
+        const int per_group = n_mtiles * group_n;
+        const int grp = tile / per_group;
+        const int rem = tile - grp * per_group;
+        const int gn = (n_ntiles - grp * group_n) < group_n ? (n_ntiles - grp * group_n) : group_n;
+        const int mt_i = rem / gn;
+        const int nt_i = grp * group_n + rem % gn;
+        const MTile mt = mtiles[mt_i];
+        const int n0 = nt_i * BN;
+        const bf16_t* Ab = A + (size_t)mt.row0 * lda;
+        const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + (size_t)n0 * K;
+        const int n_valid = (N - n0) < BN ? (N - n0) : BN;
+
+        // per-lane element offsets of the pieces this lane fetches (rows beyond the
+        // segment / matrix edge are clamped to the last valid row; their products
+        // are computed and dropped in the epilogue)
+        int offA[IAW], offB[IBW];
+#pragma unroll
+        for (int i = 0; i < IAW; ++i) {
+            const int p = (wave + i * NW) * 64 + lane;
+            const int row = p / CPR, slot = p % CPR;
+            const int r = row < mt.rows ? row : mt.rows - 1;
+            offA[i] = r * lda + ((slot ^ swz<CPR>(row)) * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < IBW; ++i) {
+            const int p = (wave + i * NW) * 64 + lane;
+            const int row = p / CPR, slot = p % CPR;
+            const int r = row < n_valid ? row : n_valid - 1;
+            offB[i] = r * K + ((slot ^ swz<CPR>(row)) * 8);
+        }
+
+        auto issue_loads = [&](int kt, int stage) {
+            unsigned char* sA = smem + stage * STAGE_BYTES;
+            unsigned char* sB = sA + A_BYTES;
+            const bf16_t* a = Ab + kt * BK;
+            const bf16_t* b = Bb + kt * BK;
+#pragma unroll
+            for (int i = 0; i < IAW; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(a + offA[i]),
+                    (__attribute__((address_space(3))) void*)(sA + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < IBW; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(b + offB[i]),
+                    (__attribute__((address_space(3))) void*)(sB + (wave + i * NW) * 1024), 16, 0, 0);
+        };
+
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        __syncthreads();  // every wavefront is done reading the previous tile's stages
+#pragma unroll
+        for (int s = 0; s < NSTAGE - 1; ++s)
+            if (s < KT) issue_loads(s, s);
+
+        // fragment read addresses (bytes inside a stage): row = base + l32, piece kk*2+half
+        const int a_row = wm * WTM + l32;
+        const int b_row = wn * WTN + l32;
+        const int sw = swz<CPR>(l32);  // rows differ by multiples of 32 -> same swizzle
+
+        for (int kt = 0; kt < KT; ++kt) {
+            if (KT - 1 - kt >= NSTAGE - 2)
+                wait_vmcnt<LPT*(NSTAGE - 2)>();
+            else
+                wait_vmcnt<0>();
+            __syncthreads();
+            if (kt + NSTAGE - 1 < KT) issue_loads(kt + NSTAGE - 1, (kt + NSTAGE - 1) % NSTAGE);
+
+            const unsigned char* sA = smem + (kt % NSTAGE) * STAGE_BYTES;
+            const unsigned char* sB = sA + A_BYTES;
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                const int piece = ((kk * 2 + half) ^ sw) * 16;
+                bf16x8 af[TM], bfr[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    af[i] = *(const bf16x8*)(sA + (a_row + i * 32) * (CPR * 16) + piece);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bfr[j] = *(const bf16x8*)(sB + (b_row + j * 32) * (CPR * 16) + piece);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+        }
+
+        // epilogue: accumulator element r of lane (l32, half) is
+        // row (r/4)*8 + half*4 + r%4, column l32 of its 32x32 tile
+        const int row_base = wm * WTM + half * 4;
+        if (SWIGLU) {
+            const int col_base = (n0 + wn * WTN) / 2 + l32;  // column in H
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jj = 0; jj < TN / 2; ++jj) {
+                    const int col = col_base + jj * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
+                        if (row < mt.rows && col < N / 2) {
+                            const float h = silu_f(acc[i][2 * jj][r]) * acc[i][2 * jj + 1][r];
+                            C[(size_t)(mt.row0 + row) * ldc + col] = f2bf(h);
+                        }
+                    }
+                }
+        } else {
+            const int col_base = n0 + wn * WTN + l32;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = col_base + j * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
+                        if (row < mt.rows && col < N) C[(size_t)(mt.row0 + row) * ldc + col] = f2bf(acc[i][j][r]);
+                    }
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// fp32 grouped GEMM (plain FMA, k ascending): 64x64 tile, 4x4 per thread
+// ---------------------------------------------------------------------------
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __restrict__ A, int lda,
+                                                                const float* __restrict__ B1,
+                                                                const float* __restrict__ B3, size_t b_stride,
+                                                                float* __restrict__ C, int ldc,
+                                                                const MTile* __restrict__ mtiles,
+                                                                const int32_t* __restrict__ n_mtiles_ptr, int N,
+                                                                int K) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float sA[BK][BM + 4];
+    __shared__ float sB1[BK][BN + 4];
+    __shared__ float sB3[SWIGLU ? BK : 1][BN + 4];
+    const int n_mtiles = n_mtiles_ptr[0];
+    const int n_ntiles = (N + BN - 1) / BN;
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;  // 16 x 16 threads, 4x4 outputs each
+    for (int tile = blockIdx.x; tile < n_mtiles * n_ntiles; tile += gridDim.x) {
+        const MTile mt = mtiles[tile / n_ntiles];
+        const int n0 = (tile % n_ntiles) * BN;
+        const float* b1 = B1 + (size_t)mt.expert * b_stride;
+        const float* b3 = SWIGLU ? B3 + (size_t)mt.expert * b_stride : nullptr;
+        float acc1[4][4] = {}, acc3[4][4] = {};
+        for (int k0 = 0; k0 < K; k0 += BK) {
+            __syncthreads();
+            for (int i = tid; i < BM * BK; i += 256) {
+                const int r = i / BK, c = i % BK;
+                const int rr = r < mt.rows ? r : mt.rows - 1;
+                sA[c][r] = (k0 + c < K) ? A[(size_t)(mt.row0 + rr) * lda + k0 + c] : 0.f;
+            }
+            for (int i = tid; i < BK * BN; i += 256) {
+                const int r = i / BN, c = i % BN;
+                const bool ok = (k0 + r < K) && (n0 + c < N);
+                sB1[r][c] = ok ? b1[(size_t)(k0 + r) * N + n0 + c] : 0.f;
+                if (SWIGLU) sB3[r][c] = ok ? b3[(size_t)(k0 + r) * N + n0 + c] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < BK; ++kk) {
+                float a[4], p[4], q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = sA[kk][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    p[j] = sB1[kk][tx * 4 + j];
+                    q[j] = SWIGLU ? sB3[kk][tx * 4 + j] : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acc1[i][j] = fmaf(a[i], p[j], acc1[i][j]);
+                        if (SWIGLU) acc3[i][j] = fmaf(a[i], q[j], acc3[i][j]);
+                    }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = ty * 4 + i, col = n0 + tx * 4 + j;
+                if (row < mt.rows && col < N) {
+                    float v = acc1[i][j];
+                    if (SWIGLU) v = v / (1.0f + expf(-v)) * acc3[i][j];
+                    C[(size_t)(mt.row0 + row) * ldc + col] = v;
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct FfnWs {
+    void* h;          // [A, ffn] hidden activations
+    MTile* tiles1;    // M-tiles for GEMM-1
+    MTile* tiles2;    // M-tiles for GEMM-2
+    int32_t* counts;  // [2] number of M-tiles
+    int capacity;
+};
+
+constexpr int kMinBM = 64;
+
+static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void* p = base ? (void*)(base + off) : nullptr;
+        off += align_up(bytes, 256);
+        return p;
+    };
+    FfnWs w;
+    w.capacity = (int)(ceil_div64(A > 0 ? A : 1, kMinBM) + nseg);
+    w.h = take((size_t)(A > 0 ? A : 1) * ffn * dtype_size(dtype));
+    w.tiles1 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
+    w.tiles2 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
+    w.counts = (int32_t*)take(256);
+    if (ws) *ws = w;
+    return off;
+}
+
+struct GemmVariant {
+    int bm, bn;
+    size_t lds;
+    int threads;
+    void (*kern)(const bf16_t*, int, const bf16_t*, size_t, bf16_t*, int, const MTile*, const int32_t*, int, int,
+                 int);
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
+static GemmVariant make_variant() {
+    GemmVariant v;
+    v.bm = BM;
+    v.bn = BN;
+    v.lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
+    v.threads = WGM * WGN * 64;
+    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, SWIGLU>;
+    return v;
+}
+
+// tile shapes built into the library; index 0 is the default
+static const GemmVariant kGemm1[] = {
+    make_variant<128, 256, 64, 2, 2, 3, true>(),
+    make_variant<256, 256, 64, 2, 2, 2, true>(),
+    make_variant<128, 512, 32, 1, 4, 3, true>(),
+    make_variant<256, 256, 64, 2, 4, 2, true>(),
+    make_variant<64, 256, 64, 1, 4, 3, true>(),
+};
+static const GemmVariant kGemm2[] = {
+    make_variant<128, 256, 64, 2, 2, 3, false>(),
+    make_variant<256, 256, 64, 2, 2, 2, false>(),
+    make_variant<128, 512, 32, 1, 4, 3, false>(),
+    make_variant<256, 256, 64, 2, 4, 2, false>(),
+    make_variant<64, 256, 64, 1, 4, 3, false>(),
+};
+constexpr int kNumVariants = sizeof(kGemm1) / sizeof(kGemm1[0]);
+
+static int env_int(const char* name, int dflt) {
+    const char* s = getenv(name);
+    return (s && *s) ? atoi(s) : dflt;
+}
+
+static int num_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, const bf16_t* Bp, size_t b_stride,
+                            bf16_t* C, int ldc, const MTile* tiles, const int32_t* n_tiles, int N, int K,
+                            int group_n, hipStream_t st) {
+    hipError_t e = hipFuncSetAttribute((const void*)v.kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds);
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return MOE_ERR_HIP;
+    }
+    const int grid = num_cus();
+    hipLaunchKernelGGL(v.kern, dim3(grid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles, n_tiles,
+                       N, K, group_n);
+    return check_launch();
+}
+
+}  // namespace moegps
+
+extern "C" size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype) {
+    if (E < 1 || d < 1 || ffn < 1) return 0;
+    return (size_t)3 * E * d * ffn * moegps::dtype_size(dtype);
+}
+
+extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype, int E, int d, int ffn,
+                                void* packed, void* stream) {
+    using namespace moegps;
+    if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
+    if (E < 1 || d < 1 || ffn < 1 || !W1 || !W3 || !W2 || !packed) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t per = (size_t)E * d * ffn;
+    if (dtype == MOE_DTYPE_F32) {
+        if ((per * 4) % 16 != 0) return MOE_ERR_UNSUPPORTED;
+        const void* src[3] = {W1, W3, W2};
+        for (int i = 0; i < 3; ++i) {
+            hipLaunchKernelGGL(copy_u4_kernel, dim3(1024), dim3(256), 0, st, (const uint4*)src[i],
+                               (uint4*)((float*)packed + i * per), per * 4 / 16);
+            int rc = check_launch();
+            if (rc != MOE_OK) return rc;
+        }
+        return MOE_OK;
+    }
+    if (d % 64 != 0 || ffn % 64 != 0) return MOE_ERR_UNSUPPORTED;
+    if (E > 65535) return MOE_ERR_UNSUPPORTED;
+    bf16_t* p13 = (bf16_t*)packed;          // [E][2*ffn][d], gate/up interleaved by 32 columns
+    bf16_t* p2 = p13 + 2 * per;             // [E][d][ffn]
+    const size_t es = (size_t)d * ffn;
+    // W1, W3: in[k = d][n = ffn] -> out[n'][d]
+    dim3 g13(ffn / 32, d / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p13, d, ffn, es, 2 * es, 1, 0);
+    int rc = check_launch();
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p13, d, ffn, es, 2 * es, 1, 1);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    // W2: in[k = ffn][n = d] -> out[n = d][k = ffn]
+    dim3 g2(d / 32, ffn / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, es, es, 0, 0);
+    return check_launch();
+}
+
+extern "C" size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype) {
+    using namespace moegps;
+    if (A < 0 || d < 1 || ffn < 1 || nseg < 1) return 0;
+    return ffn_ws_layout(A, d, ffn, nseg, dtype, nullptr, nullptr);
+}
+
+extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
+                               const int32_t* seg_offsets, const int32_t* slot_expert, int nseg, int seg_begin,
+                               int seg_end, const void* packed, void* y_perm, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    using namespace moegps;
+    if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
+    if (A < 0 || d < 1 || ffn < 1 || E < 1 || nseg < 1) return MOE_ERR_INVALID_ARG;
+    if (seg_begin < 0 || seg_end > nseg || seg_begin > seg_end) return MOE_ERR_INVALID_ARG;
+    if (nseg > MOE_MAX_SEGMENTS || A >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    if (dtype == MOE_DTYPE_BF16 && (d % 64 != 0 || ffn % 64 != 0)) return MOE_ERR_UNSUPPORTED;
+    if (dtype == MOE_DTYPE_F32 && (d % 4 != 0 || ffn % 4 != 0)) return MOE_ERR_UNSUPPORTED;
+    if ((int64_t)256 * (d > ffn ? d : ffn) >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit tile offsets
+    if (!seg_offsets || !slot_expert || !packed || !workspace) return MOE_ERR_INVALID_ARG;
+    if (A > 0 && (!x_perm || !y_perm)) return MOE_ERR_INVALID_ARG;
+    FfnWs ws;
+    const size_t need = ffn_ws_layout(A, d, ffn, nseg, dtype, (char*)workspace, &ws);
+    if (workspace_bytes < need) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (A == 0 || seg_begin == seg_end) return MOE_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t per = (size_t)E * d * ffn;
+    int rc;
+
+    if (dtype == MOE_DTYPE_F32) {
+        hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
+                           seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts);
+        if ((rc = check_launch()) != MOE_OK) return rc;
+        const float* w1 = (const float*)packed;
+        const float* w3 = w1 + per;
+        const float* w2 = w3 + per;
+        const int grid = 4 * num_cus();
+        hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), dim3(grid), dim3(256), 0, st, (const float*)x_perm, d, w1,
+                           w3, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts, ffn, d);
+        if ((rc = check_launch()) != MOE_OK) return rc;
+        hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), dim3(grid), dim3(256), 0, st, (const float*)ws.h, ffn,
+                           w2, (const float*)nullptr, (size_t)d * ffn, (float*)y_perm, d, ws.tiles1, ws.counts, d,
+                           ffn);
+        return check_launch();
+    }
+
+    int v1 = env_int("MOEGPS_FFN_TILE1", 0), v2 = env_int("MOEGPS_FFN_TILE2", 0);
+    if (v1 < 0 || v1 >= kNumVariants) v1 = 0;
+    if (v2 < 0 || v2 >= kNumVariants) v2 = 0;
+    int group_n = env_int("MOEGPS_FFN_GROUP_N", 8);
+    if (group_n < 1) group_n = 1;
+    const GemmVariant& g1 = kGemm1[v1];
+    const GemmVariant& g2 = kGemm2[v2];
+    hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
+                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
+                       E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 1);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    const bf16_t* p13 = (const bf16_t*)packed;
+    const bf16_t* p2 = p13 + 2 * per;
+    rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)2 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
+                          ws.counts, 2 * ffn, d, group_n, st);
+    if (rc != MOE_OK) return rc;
+    return launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, ws.tiles2,
+                            ws.counts + 1, d, ffn, group_n, st);
+}

@@ -1,0 +1,133 @@
+"""One MoE FFN layer with dynamic expert duplication, as a sequence of C-ABI calls.
+
+``MoELayer`` owns the device buffers (allocated once through torch) and runs the
+path route -> histogram -> duplication plan -> permute -> grouped FFN -> combine
+(the FFN side of the single-layer flow in Figure 3) with no host synchronisation
+between the calls.  Every step runs inside libmoegps; this file only sequences
+the calls and keeps the buffers.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import MODE_DISTRIBUTION, MODE_NONE, MODE_TOKEN, MoEConfig
+
+
+def torch_dtype(cfg: MoEConfig):
+    return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Storage array from ``workloads`` (float32, or uint16 bf16 bit patterns) -> GPU tensor."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+class MoELayer:
+    def __init__(self, cfg: MoEConfig, device="cuda"):
+        self.cfg = cfg
+        self.dev = torch.device(device)
+        c = cfg
+        dt = torch_dtype(c)
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        self.topk_idx = torch.empty((c.T, c.k), **i32)
+        self.topk_w = torch.empty((c.T, c.k), dtype=torch.float32, device=self.dev)
+        self.hist = torch.empty(c.E, **i32)
+        self.hist_plan = torch.empty(c.E, **i32)
+        self.slot_expert = torch.empty(c.nseg, **i32)
+        self.slot_quota = torch.empty(c.nseg, **i32)
+        self.rank_load_pred = torch.empty(c.G, **i32)
+        self.n_iters = torch.empty(1, **i32)
+        self.perm = dict(
+            seg_offsets=torch.empty(c.nseg + 1, **i32),
+            row_of_assign=torch.empty(c.A, **i32),
+            assign_of_row=torch.empty(c.A, **i32),
+            x_perm=torch.empty((c.A, c.d), dtype=dt, device=self.dev),
+            rank_load=torch.empty(c.G, **i32),
+        )
+        self.y_perm = torch.zeros((c.A, c.d), dtype=dt, device=self.dev)
+        self.out = torch.empty((c.T, c.d), dtype=dt, device=self.dev)
+        dcode = B.MOE_DTYPE_F32 if c.dtype == "f32" else B.MOE_DTYPE_BF16
+        self.ws_perm = torch.empty(max(256, B.moe_permute_workspace_bytes(c.T, c.E, c.k, c.G, c.S)),
+                                   dtype=torch.uint8, device=self.dev)
+        self.ws_ffn = torch.empty(max(256, B.moe_grouped_ffn_workspace_bytes(c.A, c.d, c.ffn, c.nseg, dcode)),
+                                  dtype=torch.uint8, device=self.dev)
+        self.packed: Optional[torch.Tensor] = None
+
+    def set_weights(self, W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor) -> None:
+        """One-off repack of the (static) expert weights."""
+        self.packed = B.moe_pack_weights(W1, W3, W2)
+
+    # individual steps (each is exactly one C-ABI call) ---------------------
+    def route(self, logits):
+        lib = B.load_library()
+        c = self.cfg
+        B._check(lib.moe_route_topk(B._ptr(logits), c.T, c.E, c.k, B._ptr(self.topk_idx), B._ptr(self.topk_w),
+                                    B._stream()), "moe_route_topk")
+
+    def histogram(self):
+        B.moe_histogram(self.topk_idx, self.cfg.E, out=self.hist)
+
+    def plan(self, mode, hist_pred: Optional[torch.Tensor], pred_idx: Optional[torch.Tensor]):
+        lib = B.load_library()
+        c = self.cfg
+        if mode == MODE_TOKEN:
+            B.moe_histogram(pred_idx, c.E, out=self.hist_plan)
+            hp = self.hist_plan
+        elif mode == MODE_DISTRIBUTION:
+            hp = hist_pred
+        else:
+            hp = self.hist
+        self._hp = hp
+        B._check(lib.moe_plan_duplicates(mode, B._ptr(hp), c.E, c.G, c.S, c.cmax, B._ptr(self.slot_expert),
+                                         B._ptr(self.slot_quota), B._ptr(self.rank_load_pred), B._ptr(self.n_iters),
+                                         B._stream()), "moe_plan_duplicates")
+
+    def permute(self, mode, x, pred_idx):
+        c = self.cfg
+        B.moe_permute(mode, x, self.topk_idx, pred_idx if mode == MODE_TOKEN else None, self.hist, self._hp,
+                      self.slot_expert, self.slot_quota, c.E, c.G, c.S, workspace=self.ws_perm, out=self.perm)
+
+    def ffn(self, seg_begin=0, seg_end=None):
+        c = self.cfg
+        if self.packed is None:
+            raise B.MoeGpsError("set_weights() first")
+        B.moe_grouped_ffn(self.perm["x_perm"], self.perm["seg_offsets"], self.slot_expert, self.packed, c.E, c.ffn,
+                          seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm)
+
+    def combine(self):
+        c = self.cfg
+        B.moe_combine(self.y_perm, self.perm["row_of_assign"], self.topk_w, c.T, c.k, out=self.out)
+
+    # the whole path -----------------------------------------------------------
+    def step(self, logits: torch.Tensor, x: torch.Tensor, hist_pred: Optional[torch.Tensor] = None,
+             pred_idx: Optional[torch.Tensor] = None, mode: Optional[int] = None) -> torch.Tensor:
+        mode = self.cfg.mode if mode is None else mode
+        self.route(logits)
+        self.histogram()
+        self.plan(mode, hist_pred, pred_idx)
+        self.permute(mode, x, pred_idx)
+        self.ffn()
+        self.combine()
+        return self.out
+
+    def load_report(self) -> dict:
+        """Host read-back (off the timed path): per-rank rows, makespan, imbalance and
+        skewness (most popular expert's tokens / average tokens per expert)."""
+        c = self.cfg
+        rank_load = self.perm["rank_load"].cpu().numpy().astype(np.int64)
+        hist = self.hist.cpu().numpy().astype(np.int64)
+        A = int(hist.sum())
+        return dict(
+            rank_load=rank_load.tolist(),
+            makespan=int(rank_load.max()) if rank_load.size else 0,
+            imbalance=float(rank_load.max() * c.G / A) if A else 0.0,
+            skewness=float(hist.max() * c.E / A) if A else 0.0,
+            n_iters=int(self.n_iters.item()),
+            replicas=int((self.slot_expert.cpu().numpy() >= 0).sum() - c.E),
+        )

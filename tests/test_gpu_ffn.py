@@ -1,0 +1,197 @@
+"""GPU parity of the grouped SwiGLU FFN and of the whole layer against the fp64 oracle.
+
+Tolerances: max|delta| <= 1e-5 * max|ref| for fp32 and <= 2e-2 * max|ref| for bf16
+storage with fp32 accumulation (hidden activation and output rounded to bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import grouped_ffn, ffn_rows, combine, moe_layer
+from paper_2506_07366_amd import binding as B
+from paper_2506_07366_amd import workloads as wl
+from paper_2506_07366_amd.layer import MoELayer, to_device
+from gpu_util import Case, dev_i32, to_host_f32, weights_storage, shape_key
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def host_weights(cfg):
+    W1s, W3s, W2s = weights_storage(shape_key(cfg))
+    return W1s, W3s, W2s
+
+
+def dev_weights(cfg, Ws):
+    return tuple(to_device(w, cfg.dtype) for w in Ws)
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def run_ffn_case(cfg, seg_sizes, slot_expert, seed=0):
+    """x_perm with the given ragged segments through the HIP FFN and the oracle."""
+    rng = np.random.default_rng(seed)
+    A = int(sum(seg_sizes))
+    x = wl.quantize(rng.standard_normal((A, cfg.d)).astype(np.float32), cfg.dtype)
+    seg_offsets = np.concatenate([[0], np.cumsum(seg_sizes)]).astype(np.int32)
+    Ws = host_weights(cfg)
+    packed = B.moe_pack_weights(*dev_weights(cfg, Ws))
+    y = B.moe_grouped_ffn(to_device(wl.to_storage(x, cfg.dtype), cfg.dtype), dev_i32(seg_offsets),
+                          dev_i32(slot_expert), packed, cfg.E, cfg.ffn)
+    Wf = [wl.from_storage(w, cfg.dtype) for w in Ws]
+    ref = grouped_ffn(x, seg_offsets, slot_expert, *Wf)
+    return to_host_f32(y), ref, seg_offsets
+
+
+@pytest.mark.parametrize("dtype,d,ffn", [("f32", 128, 256), ("f32", 36, 20), ("bf16", 128, 256), ("bf16", 512, 1024),
+                                         ("bf16", 64, 64), ("bf16", 192, 1408)])
+def test_ffn_ragged_segments(dtype, d, ffn):
+    E = 5
+    cfg = wl.MoEConfig("f", T=1, d=d, ffn=ffn, E=E, k=1, G=4, S=3, dtype=dtype, mode=0, seed=21)
+    # sizes around the tile edges (64/128/256) and empty segments; an empty slot (-1) with no rows
+    seg_sizes = [1, 0, 127, 129, 0, 256, 257, 63, 300, 0, 5, 64]
+    slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 0]
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert)
+    assert rel_err(got, ref) <= TOL[dtype]
+    # per-row check too (a wrong expert or a dropped tail row must not hide behind the global max)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL[dtype] * scale)
+
+
+def test_ffn_slot_range_only_touches_its_rows():
+    cfg = wl.MoEConfig("f", T=1, d=128, ffn=256, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
+    rng = np.random.default_rng(5)
+    seg_sizes = [40, 0, 130, 7, 0, 200, 33, 0, 64, 1, 0, 90]
+    slot_expert = [0, -1, 2, 3, -1, 4, 0, -1, 2, 3, -1, 1]
+    A = sum(seg_sizes)
+    x = wl.quantize(rng.standard_normal((A, cfg.d)).astype(np.float32), "bf16")
+    so = np.concatenate([[0], np.cumsum(seg_sizes)]).astype(np.int32)
+    Ws = host_weights(cfg)
+    packed = B.moe_pack_weights(*dev_weights(cfg, Ws))
+    xd = to_device(wl.to_storage(x, "bf16"), "bf16")
+    y_full = B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn)
+    y_rank = B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn, seg_begin=3, seg_end=6)
+    yf, yr = to_host_f32(y_full), to_host_f32(y_rank)
+    assert np.array_equal(yr[so[3]:so[6]], yf[so[3]:so[6]])
+    assert np.all(yr[:so[3]] == 0) and np.all(yr[so[6]:] == 0)
+
+
+@pytest.mark.parametrize("name", ["cfg1_tiny_f32", "mid_bf16"])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_layer_full_compare(name, mode):
+    """Whole path on configs the oracle finishes in full."""
+    cfg = wl.CONFIGS[name].replace(mode=mode, acc=0.9, sigma_pred=wl.CONFIGS[name].sigma_pred)
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    Wf = [wl.from_storage(w, cfg.dtype) for w in Ws]
+    ref = moe_layer(mode, case.logits, case.x, *Wf, cfg.k, cfg.G, cfg.S, cfg.cmax,
+                    hist_pred=case.hist_plan, pred_idx=case.pred_idx)
+    layer = MoELayer(cfg)
+    layer.set_weights(*dev_weights(cfg, Ws))
+    out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), ref["topk_idx"])
+    assert np.array_equal(layer.perm["row_of_assign"].cpu().numpy(), ref["perm"]["row_of_assign"])
+    assert np.array_equal(layer.slot_expert.cpu().numpy(), ref["plan"].slot_expert)
+    assert rel_err(to_host_f32(layer.y_perm), ref["y_perm"]) <= TOL[cfg.dtype]
+    assert rel_err(to_host_f32(out), ref["out"]) <= TOL[cfg.dtype]
+    rep = layer.load_report()
+    assert rep["makespan"] == int(ref["perm"]["rank_load"].max())
+    assert rep["n_iters"] == ref["plan"].n_iters
+
+
+FULL = ["cfg2_mixtral_dist", "cfg3_mixtral_t2e", "cfg4_finegrained", "cfg5_prefill_a1_m1", "cfg5_prefill_a0.1_m2",
+        "cfg5_prefill_a10_m0", "cfg5_decode_m1", "cfg5_decode_m0", "cfg5_decode_m2"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_layer_full_size_sampled(name):
+    """Full-size configs in the launch configuration the benchmark times: integer
+    outputs compared in full, FFN / layer outputs on sampled rows the oracle can
+    compute one by one (all k rows of sampled tokens, the first and last row of
+    every non-empty segment, rows either side of every 64-row tile boundary)."""
+    cfg = wl.CONFIGS[name]
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    layer = MoELayer(cfg)
+    layer.set_weights(*dev_weights(cfg, Ws))
+    out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), case.idx)
+    assert np.array_equal(layer.hist.cpu().numpy(), case.hist)
+    assert np.array_equal(layer.slot_expert.cpu().numpy(), case.plan.slot_expert)
+    assert np.array_equal(layer.slot_quota.cpu().numpy(), case.plan.slot_quota)
+    assert np.array_equal(layer.perm["seg_offsets"].cpu().numpy(), case.perm["seg_offsets"])
+    assert np.array_equal(layer.perm["row_of_assign"].cpu().numpy(), case.perm["row_of_assign"])
+    assert np.array_equal(layer.perm["rank_load"].cpu().numpy(), case.perm["rank_load"])
+
+    rng = np.random.default_rng(123)
+    n_tok = min(cfg.T, 128)
+    toks = np.sort(rng.choice(cfg.T, size=n_tok, replace=False))
+    roa = case.perm["row_of_assign"].reshape(cfg.T, cfg.k)
+    rows = set(roa[toks].reshape(-1).tolist())
+    so = case.perm["seg_offsets"]
+    for s in range(cfg.nseg):
+        lo, hi = int(so[s]), int(so[s + 1])
+        if hi > lo:
+            rows.update([lo, hi - 1])
+            for b in range(lo + 64, hi, 64):      # tile boundaries inside the segment
+                if rng.random() < 0.25:
+                    rows.update([b - 1, b])
+    rows = np.array(sorted(rows), dtype=np.int64)
+    aor = case.perm["assign_of_row"]
+    seg_of_row = np.searchsorted(so, rows, side="right") - 1
+    exp_of_row = case.plan.slot_expert[seg_of_row]
+    assert np.array_equal(exp_of_row, case.idx.reshape(-1)[aor[rows]])
+    y_ref = np.zeros((rows.size, cfg.d))
+    for e in np.unique(exp_of_row):
+        sel = np.nonzero(exp_of_row == e)[0]
+        xr = case.x[aor[rows[sel]] // cfg.k]
+        y_ref[sel] = ffn_rows(xr, wl.from_storage(Ws[0][e], cfg.dtype), wl.from_storage(Ws[1][e], cfg.dtype),
+                              wl.from_storage(Ws[2][e], cfg.dtype))
+    y_got = to_host_f32(layer.y_perm[torch.from_numpy(rows).cuda()])
+    scale = np.max(np.abs(y_ref))
+    assert np.all(np.max(np.abs(y_got - y_ref), axis=1) <= TOL[cfg.dtype] * scale)
+    # layer output of the sampled tokens
+    pos = {int(r): i for i, r in enumerate(rows)}
+    out_ref = np.zeros((n_tok, cfg.d))
+    for i, t in enumerate(toks):
+        for j in range(cfg.k):
+            out_ref[i] += case.w[t, j] * y_ref[pos[int(roa[t, j])]]
+    out_got = to_host_f32(out[torch.from_numpy(toks).cuda()])
+    assert np.max(np.abs(out_got - out_ref)) <= TOL[cfg.dtype] * np.max(np.abs(out_ref))
+    # properties that hold at any size
+    assert int(layer.perm["rank_load"].sum()) == cfg.A
+    assert torch.isfinite(out.float()).all()
+
+
+def test_output_independent_of_plan_mode():
+    """Replicas hold the same weights: the layer output must not depend on the plan."""
+    cfg = wl.CONFIGS["mid_bf16"]
+    Ws = host_weights(cfg)
+    outs = []
+    for mode in (0, 1, 2):
+        c = cfg.replace(mode=mode, acc=0.8)
+        case = Case(c)
+        layer = MoELayer(c)
+        layer.set_weights(*dev_weights(c, Ws))
+        out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(),
+                         pred_idx=case.dev_pred_idx())
+        outs.append(to_host_f32(out))
+    scale = np.max(np.abs(outs[0]))
+    assert np.max(np.abs(outs[1] - outs[0])) <= 2e-2 * scale
+    assert np.max(np.abs(outs[2] - outs[0])) <= 2e-2 * scale
+
+
+def test_identity_round_trip_permute_combine():
+    """permute then combine with y_perm := x_perm returns x (gate weights sum to 1)."""
+    cfg = wl.MoEConfig("rt", T=777, d=256, ffn=64, E=16, k=4, G=4, S=6, dtype="f32", mode=1, sigma_pred=0.3, seed=6)
+    case = Case(cfg)
+    x = case.dev_x()
+    idx, w = B.moe_route_topk(case.dev_logits(), cfg.k)
+    out = B.moe_permute(1, x, idx, None, dev_i32(case.hist), case.dev_hist_plan(), dev_i32(case.plan.slot_expert),
+                        dev_i32(case.plan.slot_quota), cfg.E, cfg.G, cfg.S)
+    back = B.moe_combine(out["x_perm"], out["row_of_assign"], w, cfg.T, cfg.k)
+    assert np.max(np.abs(to_host_f32(back) - case.x)) <= 1e-5 * np.max(np.abs(case.x))
