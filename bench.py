@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE FFN layer with dynamic expert duplication on one MI355X.
+
+One "step" is one pass of the whole path over one batch of seeded synthetic input
+that is already resident in HBM: route -> histogram -> duplication plan -> permute
+-> grouped SwiGLU FFN -> combine.  Prints one JSON line:
+  value      = tokens/s of the whole layer (T / time per step)
+  roofline   = the dominant kernel (the gate/up + SwiGLU grouped GEMM) against the
+               MI355X dense bf16 MFMA peak, its duration measured with HIP events on
+               the launch stream inside the timed region
+  cpu_baseline = the CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 vector peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def describe(cfg):
+    mode = {0: "no prediction", 1: "distribution-only", 2: "token-to-expert"}[cfg.mode]
+    return (f"{cfg.name}: T={cfg.T} d={cfg.d} ffn={cfg.ffn} E={cfg.E} top-{cfg.k} {cfg.dtype} "
+            f"G={cfg.G}x{cfg.S} slots, {mode} plan")
+
+
+def cpu_baseline(cfg, case_inputs, max_rows=1024):
+    """Time the oracle on the host: integer stages in full, the fp64 FFN + combine on
+    whole segments holding at most ``max_rows`` rows, scaled linearly to all rows."""
+    import oracle
+    logits, x, Ws, hist_pred, pred_idx, wl = case_inputs
+    t0 = time.perf_counter()
+    idx, w = oracle.route_topk(logits, cfg.k)
+    hist = oracle.histogram(idx, cfg.E)
+    hp = oracle.histogram(pred_idx, cfg.E) if cfg.mode == 2 else (hist_pred if cfg.mode == 1 else hist)
+    plan = oracle.plan_duplicates(cfg.mode, hp, cfg.E, cfg.G, cfg.S, cfg.cmax)
+    perm = oracle.permute(cfg.mode, x, idx, pred_idx, hist, hp, plan.slot_expert, plan.slot_quota,
+                          cfg.E, cfg.G, cfg.S)
+    t_int = time.perf_counter() - t0
+    so = perm["seg_offsets"]
+    sizes = np.diff(so)
+    order = [s for s in np.argsort(sizes, kind="stable") if sizes[s] > 0]
+    chosen, rows = [], 0
+    for s in order:                       # smallest non-empty segments first
+        if chosen and rows + sizes[s] > max_rows:
+            break
+        chosen.append(int(s))
+        rows += int(sizes[s])
+    t0 = time.perf_counter()
+    for s in chosen:
+        e = int(plan.slot_expert[s])
+        y = oracle.ffn_rows(perm["x_perm"][so[s]:so[s + 1]], wl.from_storage(Ws[0][e], cfg.dtype),
+                            wl.from_storage(Ws[1][e], cfg.dtype), wl.from_storage(Ws[2][e], cfg.dtype))
+    t_ffn = time.perf_counter() - t0
+    # combine on the same number of rows
+    nt = max(1, rows // cfg.k)
+    yy = np.zeros((nt * cfg.k, cfg.d))
+    t0 = time.perf_counter()
+    oracle.combine(yy, np.arange(nt * cfg.k), w[:nt], nt, cfg.k)
+    t_comb = time.perf_counter() - t0
+    scale = cfg.A / max(rows, 1)
+    total = t_int + (t_ffn + t_comb) * scale
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {
+        "value": cfg.T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"integer stages in full ({t_int:.2f} s); fp64 FFN + combine on {len(chosen)} whole segments = "
+                   f"{rows} of {cfg.A} rows ({t_ffn + t_comb:.2f} s), scaled linearly in rows (extrapolated)"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg2_mixtral_dist")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stages", action="store_true", help="also print per-stage timings to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the G expert-parallel ranks are emulated as "
+              "partitions of one device); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_07366_amd import binding as B
+    from paper_2506_07366_amd import workloads as wl
+    from paper_2506_07366_amd.layer import MoELayer, to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load_library()   # fails loudly if the HIP library is missing
+
+    cfg = wl.CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    logits_h = wl.gen_logits(cfg)
+    x_h = wl.gen_x(cfg)
+    Ws = wl.gen_weights_storage(cfg, threads=16)
+    logits = torch.from_numpy(logits_h).cuda()
+    x = to_device(wl.to_storage(x_h, cfg.dtype), cfg.dtype)
+    layer = MoELayer(cfg)
+    layer.set_weights(*[to_device(w, cfg.dtype) for w in Ws])
+
+    # predictions are inputs of the step: drawn on the host from the routing result
+    # of an untimed pass
+    layer.route(logits)
+    layer.histogram()
+    torch.cuda.synchronize()
+    hist_true = layer.hist.cpu().numpy()
+    hist_pred_h = wl.gen_pred_hist(cfg, hist_true) if cfg.mode == 1 else None
+    pred_idx_h = wl.gen_pred_idx(cfg, layer.topk_idx.cpu().numpy()) if cfg.mode == 2 else None
+    hist_pred = None if hist_pred_h is None else torch.from_numpy(hist_pred_h).cuda()
+    pred_idx = None if pred_idx_h is None else torch.from_numpy(pred_idx_h).cuda()
+
+    def step():
+        return layer.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # events for the dominant kernel, recorded by the library on the launch stream
+    bf16 = cfg.dtype == "bf16"
+    evs = []
+    if bf16:
+        for _ in range(args.steps):
+            quad = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            for e in quad:
+                e.record()      # creates the underlying hipEvent
+            evs.append(quad)
+        torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if bf16:
+            B.moe_grouped_ffn_time_next_call(evs[i])
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    flops1 = 4.0 * cfg.A * cfg.d * cfg.ffn      # gate + up products
+    flops2 = 2.0 * cfg.A * cfg.d * cfg.ffn      # down product
+    if bf16:
+        g1_ms = float(np.mean([q[0].elapsed_time(q[1]) for q in evs]))
+        g2_ms = float(np.mean([q[2].elapsed_time(q[3]) for q in evs]))
+        achieved = flops1 / (g1_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<swiglu> (gate/up product)",
+                    "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "avg_ms": g1_ms,
+                    "down_product": {"avg_ms": g2_ms, "achieved": flops2 / (g2_ms * 1e-3) / 1e12,
+                                     "frac": flops2 / (g2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+                    "ffn_frac_of_peak": (flops1 + flops2) / ((g1_ms + g2_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    else:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            layer.ffn()
+        e1.record()
+        torch.cuda.synchronize()
+        f_ms = e0.elapsed_time(e1) / args.steps
+        achieved = (flops1 + flops2) / (f_ms * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "grouped_gemm_f32_kernel (both products)", "achieved": achieved,
+                    "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F32_TFLOPS,
+                    "traffic": None, "avg_ms": f_ms}
+
+    # per-stage timings (outside the timed region)
+    stage_ms = {}
+    b = 2 if bf16 else 4
+
+    def time_stage(name, fn, reps=10):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        s.record()
+        for _ in range(reps):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        stage_ms[name] = s.elapsed_time(e) / reps
+
+    time_stage("route", lambda: layer.route(logits))
+    time_stage("histogram", layer.histogram)
+    time_stage("plan", lambda: layer.plan(cfg.mode, hist_pred, pred_idx))
+    time_stage("permute", lambda: layer.permute(cfg.mode, x, pred_idx))
+    time_stage("ffn", layer.ffn)
+    time_stage("combine", layer.combine)
+    bytes_permute = cfg.T * cfg.d * b + cfg.A * cfg.d * b + 16 * cfg.A
+    bytes_combine = cfg.A * cfg.d * b + 12 * cfg.A + cfg.T * cfg.d * b
+    hbm = {
+        "permute_GBs": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9,
+        "combine_GBs": bytes_combine / (stage_ms["combine"] * 1e-3) / 1e9,
+    }
+    hbm["permute_frac"] = hbm["permute_GBs"] / PEAK_HBM_GBS
+    hbm["combine_frac"] = hbm["combine_GBs"] / PEAK_HBM_GBS
+    report = layer.load_report()
+
+    result = {
+        "metric": "MoE-layer tokens/s (route+plan+permute+FFN+combine); FFN MFMA % of peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed},
+        "roofline": roofline,
+        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, (logits_h, x_h, Ws, hist_pred_h, pred_idx_h, wl))
+    if args.stages:
+        print(json.dumps(stage_ms, indent=1), file=sys.stderr)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -176,6 +176,15 @@ int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, in
                     void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Optional timing hook for the next moe_grouped_ffn call on this host thread:
+ * events[0..3] are hipEvent_t handles (as void*) that the call records on its
+ * stream before and after its first product (gate/up + SwiGLU) and before and
+ * after its second product (down).  The hook is consumed by that one call.
+ * Pass NULL to clear it.  `events` is a HOST array of 4 handles; it is copied.
+ */
+int moe_grouped_ffn_time_next_call(void* const* events);
+
+/*
  * Weighted un-permute (stands where the all-to-all after the FFN is):
  *     out[t, :] = sum_{j<k} topk_w[t, j] * y_perm[row_of_assign[t*k + j], :]
  * summed in fp32 with j ascending; bf16 output is rounded once at the end.

@@ -24,7 +24,8 @@ MODE_NONE, MODE_DISTRIBUTION, MODE_TOKEN = 0, 1, 2
 EXPORTS = [
     "moe_strerror", "moe_last_hip_error", "moe_abi_version", "moe_route_topk", "moe_histogram",
     "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_packed_weights_bytes",
-    "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_combine",
+    "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_time_next_call",
+    "moe_combine",
 ]
 
 
@@ -73,6 +74,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn.restype = c_int
     lib.moe_grouped_ffn.argtypes = [vp, c_int, c_i64, c_int, c_int, c_int, vp, vp, c_int, c_int, c_int,
                                     vp, vp, vp, c_sz, vp]
+    lib.moe_grouped_ffn_time_next_call.restype = c_int
+    lib.moe_grouped_ffn_time_next_call.argtypes = [ctypes.POINTER(vp)]
     lib.moe_combine.restype = c_int
     lib.moe_combine.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp]
     if path is None:
@@ -246,3 +249,14 @@ def moe_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_w: torch
     _check(lib.moe_combine(_ptr(y_perm), dt, T, d, k, _ptr(row_of_assign), _ptr(topk_w), _ptr(out), _stream()),
            "moe_combine")
     return out
+
+
+def moe_grouped_ffn_time_next_call(events) -> None:
+    """``events``: four recorded-once ``torch.cuda.Event(enable_timing=True)``; the next
+    moe_grouped_ffn call on this thread records them around its two products."""
+    lib = load_library()
+    if events is None:
+        _check(lib.moe_grouped_ffn_time_next_call(None), "moe_grouped_ffn_time_next_call")
+        return
+    arr = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    _check(lib.moe_grouped_ffn_time_next_call(arr), "moe_grouped_ffn_time_next_call")
