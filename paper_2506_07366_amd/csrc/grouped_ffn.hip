@@ -17,8 +17,8 @@
 //
 // fp32 path (small reference-precision configs): a plain LDS-tiled FMA kernel.
 #include "common.h"
-#include "block_scan.h"
 #include <stdlib.h>
+#include <type_traits>
 
 namespace moegps {
 
@@ -72,34 +72,45 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
                                                              const int32_t* __restrict__ slot_expert, int seg_begin,
                                                              int seg_end, int E, int BM, MTile* __restrict__ tiles,
                                                              int capacity, int32_t* __restrict__ n_tiles) {
-    __shared__ int cnt[MOE_MAX_SEGMENTS + 1];
-    __shared__ int wave_sum[16];
+    // Tiles are listed by (expert, segment): tiles that are neighbours in the table
+    // mostly read the same expert's weights.
+    __shared__ int cnt[MOE_MAX_SEGMENTS];
+    __shared__ int ex[MOE_MAX_SEGMENTS];
+    __shared__ int total_s;
     const int ns = seg_end - seg_begin;
+    if (threadIdx.x == 0) total_s = 0;
+    __syncthreads();
     for (int i = threadIdx.x; i < ns; i += blockDim.x) {
         const int s = seg_begin + i;
         const int rows = seg_offsets[s + 1] - seg_offsets[s];
         const int e = slot_expert[s];
-        cnt[i] = (rows > 0 && e >= 0 && e < E) ? (rows + BM - 1) / BM : 0;
+        const int c = (rows > 0 && e >= 0 && e < E) ? (rows + BM - 1) / BM : 0;
+        cnt[i] = c;
+        ex[i] = e;
+        if (c) atomicAdd(&total_s, c);
     }
     __syncthreads();
-    block_exclusive_scan_2048(cnt, ns, wave_sum);
     for (int i = threadIdx.x; i < ns; i += blockDim.x) {
+        const int nt = cnt[i];
+        if (nt == 0) continue;
+        int base = 0;
+        for (int j = 0; j < ns; ++j)
+            if (ex[j] < ex[i] || (ex[j] == ex[i] && j < i)) base += cnt[j];
         const int s = seg_begin + i;
         const int lo = seg_offsets[s], hi = seg_offsets[s + 1];
-        const int nt = cnt[i + 1] - cnt[i];
         for (int t = 0; t < nt; ++t) {
-            const int slot = cnt[i] + t;
+            const int slot = base + t;
             if (slot < capacity) {
                 MTile mt;
                 mt.row0 = lo + t * BM;
                 mt.rows = (hi - mt.row0) < BM ? (hi - mt.row0) : BM;
-                mt.expert = slot_expert[s];
+                mt.expert = ex[i];
                 mt.seg = s;
                 tiles[slot] = mt;
             }
         }
     }
-    if (threadIdx.x == 0) n_tiles[0] = cnt[ns] < capacity ? cnt[ns] : capacity;
+    if (threadIdx.x == 0) n_tiles[0] = total_s < capacity ? total_s : capacity;
 }
 
 // ---------------------------------------------------------------------------
@@ -116,12 +127,15 @@ __device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-// 16-byte piece `slot` of LDS row `row` holds global piece slot ^ swz(row): spreads
-// the 32 rows one fragment read touches over all banks
+// 16-byte piece `slot` of LDS row `row` holds global piece slot ^ swz(row).  The LDS
+// has 64 four-byte banks and serves a ds_read_b128 sixteen lanes at a time, so the
+// 16 consecutive rows one such group touches must land on 16 distinct 16-byte bank
+// groups of a 256-byte span: with 128-byte rows that is (row&1, slot) -> xor with
+// (row>>1)&7; with 64-byte rows (row&3, slot) -> xor with (row>>2)&3.
 template <int CPR>
 __device__ __forceinline__ int swz(int row) {
-    if (CPR == 8) return row & 7;
-    if (CPR == 4) return (row >> 1) & 3;
+    if (CPR == 8) return (row >> 1) & 7;
+    if (CPR == 4) return (row >> 2) & 3;
     return 0;
 }
 
@@ -145,6 +159,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA tiles");
     static_assert(!SWIGLU || (WTN % 64 == 0), "gate/up pairs must sit in one wavefront");
     static_assert(LPT * (NSTAGE - 1) < 64, "vmcnt range");
+    // With two stages every wait drains all loads, so loads of rows past the end of a
+    // ragged M-tile can simply be left out; with deeper prefetch the wait counts a fixed
+    // number of loads per k-tile and such rows are clamped to the last valid row instead.
+    constexpr bool SKIP_TAIL_LOADS = (NSTAGE == 2);
+    constexpr int ROWS_PER_LOAD = 64 / CPR;
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -156,18 +175,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
 
     const int n_mtiles = n_mtiles_ptr[0];
     const int n_ntiles = (N + BN - 1) / BN;
-    const int total = n_mtiles * n_ntiles;
     const int KT = K / BK;
 
-    for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        // (M-tile, N-tile) of this tile id: N-tiles in groups of group_n, M fastest
-        // inside a group, so concurrently running tiles share weight panels
-        const int per_group = n_mtiles * group_n;
-        const int grp = tile / per_group;
-        const int rem = tile - grp * per_group;
-        const int gn = (n_ntiles - grp * group_n) < group_n ? (n_ntiles - grp * group_n) : group_n;
-        const int mt_i = rem / gn;
-        const int nt_i = grp * group_n + rem % gn;
+    // Tile order.  Tiles are numbered in groups of group_n neighbouring N-tiles; inside
+    // a group the N-tile index runs fastest, then the M-tile (M-tiles are sorted by
+    // expert), so 32 consecutive tiles form a patch of about 32/group_n x group_n tiles
+    // that share their activation and weight panels.  Workgroups are dealt to the 8 XCDs
+    // round-robin (workgroup b runs on XCD b % 8) and every XCD has its own L2, so the
+    // 32 workgroups of one XCD take one such run of 32 consecutive tiles at a time and
+    // share its panels through that L2; the 8 XCDs take 8 consecutive runs (further
+    // along M under the same weight panels, shared through the memory-side cache).
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per_xcd = (int)(gridDim.x >> 3);
+    const int total = n_mtiles * n_ntiles;
+    const int per_group = n_mtiles * group_n;
+    for (int chunk = xcd; chunk * per_xcd < total; chunk += 8) {
+        const int t = chunk * per_xcd + slot;
+        if (t >= total) continue;  // uniform over the workgroup
+        const int grp = t / per_group;
+        const int rem = t - grp * per_group;
+        const int gw = (n_ntiles - grp * group_n) < group_n ? (n_ntiles - grp * group_n) : group_n;
+        const int mt_i = rem / gw;
+        const int nt_i = grp * group_n + rem % gw;
         const MTile mt = mtiles[mt_i];
         const int n0 = nt_i * BN;
         const bf16_t* Ab = A + (size_t)mt.row0 * lda;
@@ -200,9 +229,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             const bf16_t* b = Bb + kt * BK;
 #pragma unroll
             for (int i = 0; i < IAW; ++i)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(a + offA[i]),
-                    (__attribute__((address_space(3))) void*)(sA + (wave + i * NW) * 1024), 16, 0, 0);
+                if (!SKIP_TAIL_LOADS || (wave + i * NW) * ROWS_PER_LOAD < mt.rows)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(a + offA[i]),
+                        (__attribute__((address_space(3))) void*)(sA + (wave + i * NW) * 1024), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < IBW; ++i)
                 __builtin_amdgcn_global_load_lds(
@@ -210,6 +240,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                     (__attribute__((address_space(3))) void*)(sB + (wave + i * NW) * 1024), 16, 0, 0);
         };
 
+        // Accumulators hold the transposed product: the weight fragment is the MFMA's
+        // row operand and the activation fragment its column operand, so element r of
+        // lane (l32, half) in tile (i, j) is output row i*32 + l32 and output column
+        // j*32 + (r/4)*8 + half*4 + r%4: four consecutive columns per lane.
         f32x16 acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -218,7 +252,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        __syncthreads();  // every wavefront is done reading the previous tile's stages
+        __builtin_amdgcn_s_barrier();  // every wavefront is done reading the previous tile's stages
 #pragma unroll
         for (int s = 0; s < NSTAGE - 1; ++s)
             if (s < KT) issue_loads(s, s);
@@ -226,68 +260,100 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // fragment read addresses (bytes inside a stage): row = base + l32, piece kk*2+half
         const int a_row = wm * WTM + l32;
         const int b_row = wn * WTN + l32;
+        // 32-row sub-tiles of this wavefront that hold at least one valid row; the others
+        // (past the end of a ragged M-tile) are neither read nor multiplied
+        const int rows_w = mt.rows - wm * WTM;
+        const int tm_valid = rows_w <= 0 ? 0 : (rows_w >= WTM ? TM : (rows_w + 31) / 32);
         const int sw = swz<CPR>(l32);  // rows differ by multiples of 32 -> same swizzle
+        constexpr int KK = BK / 16;
 
-        for (int kt = 0; kt < KT; ++kt) {
-            if (KT - 1 - kt >= NSTAGE - 2)
-                wait_vmcnt<LPT*(NSTAGE - 2)>();
-            else
-                wait_vmcnt<0>();
-            __syncthreads();
-            if (kt + NSTAGE - 1 < KT) issue_loads(kt + NSTAGE - 1, (kt + NSTAGE - 1) % NSTAGE);
+        // The K loop exists twice: FULL (every 32-row sub-tile of this wavefront is valid,
+        // no conditions inside the loop) and ragged (sub-tiles i >= tm_valid are skipped).
+        // Both run the same sequence of barriers, so wavefronts of one workgroup may take
+        // different versions.
+        auto k_loop = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            for (int kt = 0; kt < KT; ++kt) {
+                // this wavefront's pieces of k-tile kt have landed; the barrier extends that
+                // to every wavefront's pieces and also says all of them finished reading the
+                // stage that the next prefetch overwrites
+                if (KT - 1 - kt >= NSTAGE - 2)
+                    wait_vmcnt<LPT*(NSTAGE - 2)>();
+                else
+                    wait_vmcnt<0>();
+                __builtin_amdgcn_s_barrier();
 
-            const unsigned char* sA = smem + (kt % NSTAGE) * STAGE_BYTES;
-            const unsigned char* sB = sA + A_BYTES;
+                const unsigned char* sA = smem + (kt % NSTAGE) * STAGE_BYTES;
+                const unsigned char* sB = sA + A_BYTES;
+                bf16x8 af[2][TM], bfr[2][TN];
+                auto load_frags = [&](int kk, int buf) {
+                    const int piece = ((kk * 2 + half) ^ sw) * 16;
 #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                const int piece = ((kk * 2 + half) ^ sw) * 16;
-                bf16x8 af[TM], bfr[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    af[i] = *(const bf16x8*)(sA + (a_row + i * 32) * (CPR * 16) + piece);
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bfr[j] = *(const bf16x8*)(sB + (b_row + j * 32) * (CPR * 16) + piece);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i)
+                        if (FULL || i < tm_valid)
+                            af[buf][i] = *(const bf16x8*)(sA + (a_row + i * 32) * (CPR * 16) + piece);
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                        bfr[buf][j] = *(const bf16x8*)(sB + (b_row + j * 32) * (CPR * 16) + piece);
+                };
+                // Fragments are double-buffered in registers: the LDS reads of step kk+1 and
+                // the global->LDS prefetch are issued ahead of the MFMAs of step kk and
+                // complete in their shadow.  sched_barrier pins that order.
+                load_frags(0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    if (kk + 1 < KK) load_frags(kk + 1, (kk + 1) & 1);
+                    if (kk == 0 && kt + NSTAGE - 1 < KT)
+                        issue_loads(kt + NSTAGE - 1, (kt + NSTAGE - 1) % NSTAGE);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        if (FULL || i < tm_valid) {
+#pragma unroll
+                            for (int j = 0; j < TN; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i],
+                                                                                    acc[i][j], 0, 0, 0);
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-        }
+        };
+        if (tm_valid == TM)
+            k_loop(std::true_type{});
+        else
+            k_loop(std::false_type{});
 
-        // epilogue: accumulator element r of lane (l32, half) is
-        // row (r/4)*8 + half*4 + r%4, column l32 of its 32x32 tile
-        const int row_base = wm * WTM + half * 4;
-        if (SWIGLU) {
-            const int col_base = (n0 + wn * WTN) / 2 + l32;  // column in H
+        // epilogue: 4 consecutive columns per lane and accumulator group -> 8-byte stores
+        const int col_w = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN)) + half * 4;
+        const int n_out = SWIGLU ? N / 2 : N;
+        constexpr int TNO = SWIGLU ? TN / 2 : TN;  // 32-column tiles of output per wavefront
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            const int row = wm * WTM + i * 32 + l32;
+            if (row < mt.rows) {
+                bf16_t* crow = C + (size_t)(mt.row0 + row) * ldc + col_w;
 #pragma unroll
-                for (int jj = 0; jj < TN / 2; ++jj) {
-                    const int col = col_base + jj * 32;
+                for (int jo = 0; jo < TNO; ++jo) {
+                    if (col_w - half * 4 + jo * 32 < n_out) {  // whole 32-column tile in range (n_out % 32 == 0)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
-                        if (row < mt.rows && col < N / 2) {
-                            const float h = silu_f(acc[i][2 * jj][r]) * acc[i][2 * jj + 1][r];
-                            C[(size_t)(mt.row0 + row) * ldc + col] = f2bf(h);
+                        for (int g = 0; g < 4; ++g) {
+                            float v[4];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                if (SWIGLU)
+                                    v[c] = silu_f(acc[i][2 * jo][g * 4 + c]) * acc[i][2 * jo + 1][g * 4 + c];
+                                else
+                                    v[c] = acc[i][jo][g * 4 + c];
+                            }
+                            uint2 o;
+                            o.x = (unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16);
+                            o.y = (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16);
+                            *(uint2*)(crow + jo * 32 + g * 8) = o;
                         }
                     }
                 }
-        } else {
-            const int col_base = n0 + wn * WTN + l32;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = col_base + j * 32;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
-                        if (row < mt.rows && col < N) C[(size_t)(mt.row0 + row) * ldc + col] = f2bf(acc[i][j][r]);
-                    }
-                }
+            }
         }
     }
 }
@@ -376,6 +442,7 @@ struct FfnWs {
 };
 
 constexpr int kMinBM = 64;
+constexpr int kGemmGrid = 256;  // persistent workgroups: 8 XCDs x 32
 
 static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
     size_t off = 0;
@@ -420,6 +487,8 @@ static const GemmVariant kGemm1[] = {
     make_variant<128, 512, 32, 1, 4, 3, true>(),
     make_variant<256, 256, 64, 2, 4, 2, true>(),
     make_variant<64, 256, 64, 1, 4, 3, true>(),
+    make_variant<256, 256, 32, 2, 4, 4, true>(),
+    make_variant<128, 256, 64, 2, 4, 3, true>(),
 };
 static const GemmVariant kGemm2[] = {
     make_variant<128, 256, 64, 2, 2, 3, false>(),
@@ -427,6 +496,8 @@ static const GemmVariant kGemm2[] = {
     make_variant<128, 512, 32, 1, 4, 3, false>(),
     make_variant<256, 256, 64, 2, 4, 2, false>(),
     make_variant<64, 256, 64, 1, 4, 3, false>(),
+    make_variant<256, 256, 32, 2, 4, 4, false>(),
+    make_variant<128, 256, 64, 2, 4, 3, false>(),
 };
 constexpr int kNumVariants = sizeof(kGemm1) / sizeof(kGemm1[0]);
 
@@ -459,9 +530,9 @@ static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, cons
         set_last_hip_error(e);
         return MOE_ERR_HIP;
     }
-    const int grid = num_cus();
-    hipLaunchKernelGGL(v.kern, dim3(grid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles, n_tiles,
-                       N, K, group_n);
+    // 32 workgroups for each of the 8 XCDs; the kernel walks the tile space itself
+    hipLaunchKernelGGL(v.kern, dim3(kGemmGrid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles,
+                       n_tiles, N, K, group_n);
     return check_launch();
 }
 
@@ -553,7 +624,7 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
         return check_launch();
     }
 
-    int v1 = env_int("MOEGPS_FFN_TILE1", 0), v2 = env_int("MOEGPS_FFN_TILE2", 0);
+    int v1 = env_int("MOEGPS_FFN_TILE1", 3), v2 = env_int("MOEGPS_FFN_TILE2", 3);
     if (v1 < 0 || v1 >= kNumVariants) v1 = 0;
     if (v2 < 0 || v2 >= kNumVariants) v2 = 0;
     int group_n = env_int("MOEGPS_FFN_GROUP_N", 8);
