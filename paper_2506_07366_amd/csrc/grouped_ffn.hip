@@ -634,9 +634,15 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
                        E, g1.bm, ws.tiles1, ws.capacity, ws.counts);
     if ((rc = check_launch()) != MOE_OK) return rc;
-    hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
-                       E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 1);
-    if ((rc = check_launch()) != MOE_OK) return rc;
+    const MTile* tiles2 = ws.tiles1;
+    const int32_t* count2 = ws.counts;
+    if (g2.bm != g1.bm) {  // the second product walks its own M-tiles only if its tile height differs
+        hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
+                           seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 1);
+        if ((rc = check_launch()) != MOE_OK) return rc;
+        tiles2 = ws.tiles2;
+        count2 = ws.counts + 1;
+    }
     const bf16_t* p13 = (const bf16_t*)packed;
     const bf16_t* p2 = p13 + 2 * per;
     const bool timed = g_time_armed;
@@ -647,8 +653,8 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
-    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, ws.tiles2,
-                          ws.counts + 1, d, ffn, group_n, st);
+    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, tiles2, count2,
+                          d, ffn, group_n, st);
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
 }

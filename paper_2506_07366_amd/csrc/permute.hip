@@ -127,20 +127,45 @@ __global__ __launch_bounds__(kPermThreads) void perm_count_kernel(const int32_t*
     for (int e = threadIdx.x; e < E; e += blockDim.x) bh1[(size_t)blockIdx.x * E + e] = bins[e];
 }
 
-// chunk bases per expert (in place) and the replica tables of the plan
+// inclusive prefix sum over the 64 lanes of a wavefront (every lane active)
+__device__ __forceinline__ long long wave_incl_scan(long long v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        const long long o = __shfl_up(v, m, kWave);
+        if (lane >= m) v += o;
+    }
+    return v;
+}
+
+// In-place exclusive scan down one column of a [nb, ncols] table by one wavefront
+// (lanes take consecutive rows); returns the column total.
+__device__ __forceinline__ int wave_column_scan(int32_t* table, int nb, int ncols, int col) {
+    const int lane = threadIdx.x & (kWave - 1);
+    int carry = 0;
+    for (int b0 = 0; b0 < nb; b0 += kWave) {
+        const int b = b0 + lane;
+        const int c = b < nb ? table[(size_t)b * ncols + col] : 0;
+        const int incl = (int)wave_incl_scan(c);
+        if (b < nb) table[(size_t)b * ncols + col] = carry + incl - c;
+        carry += __shfl(incl, kWave - 1, kWave);
+    }
+    return carry;
+}
+
+// chunk bases per expert (in place) and the replica tables of the plan; one
+// wavefront per expert column
 __global__ __launch_bounds__(1024) void perm_scan1_kernel(int mode, int nb, int E, int G, int S,
                                                            const int32_t* __restrict__ hist_true,
                                                            const int32_t* __restrict__ hist_pred,
                                                            const int32_t* __restrict__ slot_expert,
                                                            const int32_t* __restrict__ slot_quota, PermWs ws) {
     const int nseg = G * S;
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        int run = 0;
-        for (int b = 0; b < nb; ++b) {
-            const int c = ws.bh1[(size_t)b * E + e];
-            ws.bh1[(size_t)b * E + e] = run;
-            run += c;
-        }
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    for (int e = wave; e < E; e += nwaves) {
+        wave_column_scan(ws.bh1, nb, E, e);
         // replicas of e in ascending slot id with the upper bound of their range
         long long n_true = 0, n_hat = 0;
         if (mode == MOE_MODE_DISTRIBUTION) {
@@ -150,18 +175,25 @@ __global__ __launch_bounds__(1024) void perm_scan1_kernel(int mode, int nb, int 
         int cnt = 0;
         long long cum = 0;
         if (!(mode == MOE_MODE_DISTRIBUTION && n_hat <= 0)) {
-            for (int sigma = 0; sigma < nseg && cnt < G; ++sigma) {
-                if (slot_expert[sigma] != e) continue;
-                cum += slot_quota[sigma];
-                long long hi = cum;
-                if (mode == MOE_MODE_DISTRIBUTION) hi = (n_true * cum) / n_hat;  // floor(n_e * Q_r / nhat_e)
-                if (hi > 0x7fffffffLL) hi = 0x7fffffffLL;
-                ws.rep_slot[(size_t)e * G + cnt] = sigma;
-                ws.rep_hi[(size_t)e * G + cnt] = (int)hi;
-                ++cnt;
+            for (int s0 = 0; s0 < nseg; s0 += kWave) {
+                const int sigma = s0 + lane;
+                const bool match = sigma < nseg && slot_expert[sigma] == e;
+                const long long qv = match ? (long long)slot_quota[sigma] : 0ll;
+                const long long incl = wave_incl_scan(qv);
+                const unsigned long long m = __ballot(match);
+                const int pos = cnt + __popcll(m & lt);
+                if (match && pos < G) {
+                    long long hi = cum + incl;                                       // Q_{r+1}
+                    if (mode == MOE_MODE_DISTRIBUTION) hi = (n_true * hi) / n_hat;   // floor(n_e * Q / nhat_e)
+                    if (hi > 0x7fffffffLL) hi = 0x7fffffffLL;
+                    ws.rep_slot[(size_t)e * G + pos] = sigma;
+                    ws.rep_hi[(size_t)e * G + pos] = (int)hi;
+                }
+                cnt += __popcll(m);
+                cum += __shfl(incl, kWave - 1, kWave);
             }
         }
-        ws.rep_cnt[e] = cnt;
+        if (lane == 0) ws.rep_cnt[e] = cnt < G ? cnt : G;
     }
 }
 
@@ -244,14 +276,10 @@ __global__ __launch_bounds__(1024) void perm_scan2_kernel(int nb, int G, int S, 
     __shared__ int wave_sum[16];
     const int nseg = G * S;
     const int tid = threadIdx.x;
-    for (int s = tid; s < nseg; s += blockDim.x) {
-        int run = 0;
-        for (int b = 0; b < nb; ++b) {
-            const int c = ws.bh2[(size_t)b * nseg + s];
-            ws.bh2[(size_t)b * nseg + s] = run;
-            run += c;
-        }
-        tot[s] = run;
+    const int wave = tid / kWave, nwaves = blockDim.x / kWave;
+    for (int s = wave; s < nseg; s += nwaves) {  // one wavefront per segment column
+        const int total = wave_column_scan(ws.bh2, nb, nseg, s);
+        if ((tid & (kWave - 1)) == 0) tot[s] = total;
     }
     __syncthreads();
     block_exclusive_scan_2048(tot, nseg, wave_sum);
