@@ -19,6 +19,7 @@
 #include "common.h"
 #include <stdlib.h>
 #include <type_traits>
+#include <utility>
 
 namespace moegps {
 
@@ -123,6 +124,31 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xf) | (0x7 << 4) | (0xf << 8) | ((N >> 4) << 14));
 }
 
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// LDS fragment read issued as an instruction of its own: the compiler does not track
+// when the data lands, the kernel waits with lds_wait<N>() ("at most N LDS reads of
+// this wavefront still in flight"; LDS reads complete in issue order) and then ties
+// the destination registers with lds_landed() before they are used.
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(bf16x8& dst, unsigned addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_wait() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));  // vmcnt and expcnt untouched
+}
+__device__ __forceinline__ void lds_landed(bf16x8& v) { asm volatile("" : "+v"(v)); }
+
 __device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
@@ -158,7 +184,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     static_assert(IA % NW == 0 && IB % NW == 0, "tile loads must divide over the wavefronts");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA tiles");
     static_assert(!SWIGLU || (WTN % 64 == 0), "gate/up pairs must sit in one wavefront");
-    static_assert(LPT * (NSTAGE - 1) < 64, "vmcnt range");
+    static_assert(LPT * NSTAGE < 64, "vmcnt range");
+    static_assert((BK / 16) % 2 == 0, "fragment buffers alternate with an even number of steps per k-tile");
     // With two stages every wait drains all loads, so loads of rows past the end of a
     // ragged M-tile can simply be left out; with deeper prefetch the wait counts a fixed
     // number of loads per k-tile and such rows are clamped to the last valid row instead.
@@ -254,7 +281,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
 
         __builtin_amdgcn_s_barrier();  // every wavefront is done reading the previous tile's stages
 #pragma unroll
-        for (int s = 0; s < NSTAGE - 1; ++s)
+        for (int s = 0; s < NSTAGE; ++s)
             if (s < KT) issue_loads(s, s);
 
         // fragment read addresses (bytes inside a stage): row = base + l32, piece kk*2+half
@@ -271,41 +298,68 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // no conditions inside the loop) and ragged (sub-tiles i >= tm_valid are skipped).
         // Both run the same sequence of barriers, so wavefronts of one workgroup may take
         // different versions.
+        const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
         auto k_loop = [&](auto full_tag) {
             constexpr bool FULL = decltype(full_tag)::value;
+            constexpr int ROW_BYTES = CPR * 16;
+            bf16x8 af[2][TM], bfr[2][TN];
+            auto load_frags = [&](int kt, int kk, int buf) {
+                const unsigned stage = lds_base + (kt % NSTAGE) * STAGE_BYTES;
+                const unsigned piece = (unsigned)(((kk * 2 + half) ^ sw) * 16);
+                static_for<TM>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    if (FULL || i < tm_valid)
+                        lds_read_b128<i * 32 * ROW_BYTES>(af[buf][i], stage + a_row * ROW_BYTES + piece);
+                });
+                static_for<TN>([&](auto J) {
+                    constexpr int j = decltype(J)::value;
+                    lds_read_b128<j * 32 * ROW_BYTES>(bfr[buf][j], stage + A_BYTES + b_row * ROW_BYTES + piece);
+                });
+            };
+            auto frags_landed = [&](int buf) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) lds_landed(af[buf][i]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) lds_landed(bfr[buf][j]);
+            };
+            // The loop is software-pipelined across the k-tile barrier.  Fragments are
+            // double-buffered in registers; the LDS reads of step kk+1 are issued ahead of the
+            // MFMAs of step kk, which wait only for their own fragments.  The barrier that
+            // hands over k-tile kt+1 sits before the LAST step of k-tile kt: after it the
+            // wavefront reads the first fragments of k-tile kt+1 and refills the stage that
+            // k-tile kt occupied (all of its fragments are in registers by then), and the
+            // MFMAs of the last step cover both.
+            if ((!SKIP_TAIL_LOADS || mt.rows == BM) && KT >= NSTAGE)
+                wait_vmcnt<LPT*(NSTAGE - 1)>();  // k-tile 0 landed, the others may be in flight
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            load_frags(0, 0, 0);
             for (int kt = 0; kt < KT; ++kt) {
-                // this wavefront's pieces of k-tile kt have landed; the barrier extends that
-                // to every wavefront's pieces and also says all of them finished reading the
-                // stage that the next prefetch overwrites
-                if (KT - 1 - kt >= NSTAGE - 2)
-                    wait_vmcnt<LPT*(NSTAGE - 2)>();
-                else
-                    wait_vmcnt<0>();
-                __builtin_amdgcn_s_barrier();
-
-                const unsigned char* sA = smem + (kt % NSTAGE) * STAGE_BYTES;
-                const unsigned char* sB = sA + A_BYTES;
-                bf16x8 af[2][TM], bfr[2][TN];
-                auto load_frags = [&](int kk, int buf) {
-                    const int piece = ((kk * 2 + half) ^ sw) * 16;
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        if (FULL || i < tm_valid)
-                            af[buf][i] = *(const bf16x8*)(sA + (a_row + i * 32) * (CPR * 16) + piece);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        bfr[buf][j] = *(const bf16x8*)(sB + (b_row + j * 32) * (CPR * 16) + piece);
-                };
-                // Fragments are double-buffered in registers: the LDS reads of step kk+1 and
-                // the global->LDS prefetch are issued ahead of the MFMAs of step kk and
-                // complete in their shadow.  sched_barrier pins that order.
-                load_frags(0, 0);
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk) {
-                    if (kk + 1 < KK) load_frags(kk + 1, (kk + 1) & 1);
-                    if (kk == 0 && kt + NSTAGE - 1 < KT)
-                        issue_loads(kt + NSTAGE - 1, (kt + NSTAGE - 1) % NSTAGE);
+                    if (kk + 1 < KK) {
+                        load_frags(kt, kk + 1, (kk + 1) & 1);
+                        if (FULL)
+                            lds_wait<TM + TN>();
+                        else
+                            lds_wait<0>();
+                    } else {
+                        lds_wait<0>();  // every fragment of k-tile kt is in registers
+                        if (kt + 1 < KT) {
+                            // this wavefront's pieces of k-tile kt+1 have landed; the barrier
+                            // extends that to every wavefront's pieces and says all of them are
+                            // done with k-tile kt's stage
+                            if (KT - 2 - kt >= NSTAGE - 2)
+                                wait_vmcnt<LPT*(NSTAGE - 2)>();
+                            else
+                                wait_vmcnt<0>();
+                            __builtin_amdgcn_s_barrier();
+                            load_frags(kt + 1, 0, 0);
+                            if (kt + NSTAGE < KT) issue_loads(kt + NSTAGE, kt % NSTAGE);
+                        }
+                    }
+                    frags_landed(kk & 1);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
