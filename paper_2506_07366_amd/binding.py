@@ -41,7 +41,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or LIB_PATH
+    p = path or os.environ.get("MOEGPS_LIB") or LIB_PATH
     if not os.path.exists(p):
         raise MoeGpsError(
             f"{p} is missing: build it first with `python -m paper_2506_07366_amd.build` "

@@ -14,11 +14,12 @@ __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
     return __builtin_bit_cast(unsigned short, (__bf16)f);  // round to nearest even
 }
 
-template <bool BF16>
+template <bool BF16, int UNROLL>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y_perm,
                                                        const int32_t* __restrict__ row_of_assign,
                                                        const float* __restrict__ topk_w, uint4* __restrict__ out,
                                                        int T, int k, int chunks) {
+    typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
     const int lane = threadIdx.x & (kWave - 1);
     const int t = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
     if (t >= T) return;
@@ -29,40 +30,60 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
         rows[j] = j < k ? row_of_assign[(size_t)t * k + j] : 0;
         w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
     }
-    for (int c = lane; c < chunks; c += kWave) {
-        constexpr int N = BF16 ? 8 : 4;
-        float acc[N];
+    const u32x4* src = (const u32x4*)y_perm;
+    constexpr int N = BF16 ? 8 : 4;
+    // UNROLL 16-byte pieces per lane and step keep k * UNROLL row reads in flight; every
+    // byte is touched once, so loads and stores are non-temporal
+    for (int c0 = lane; c0 < chunks; c0 += kWave * UNROLL) {
+        float acc[UNROLL][N];
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] = 0.f;
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[u][i] = 0.f;
 #pragma unroll
         for (int j = 0; j < MOE_MAX_TOPK; ++j) {
             if (j < k) {
-                const uint4 v = y_perm[(size_t)rows[j] * chunks + c];
-                const unsigned u[4] = {v.x, v.y, v.z, v.w};
+                u32x4 v[UNROLL];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (BF16) {
-                        acc[2 * i] = fmaf(w[j], bf16_bits_to_float((unsigned short)(u[i] & 0xffffu)), acc[2 * i]);
-                        acc[2 * i + 1] = fmaf(w[j], bf16_bits_to_float((unsigned short)(u[i] >> 16)), acc[2 * i + 1]);
-                    } else {
-                        acc[i] = fmaf(w[j], __builtin_bit_cast(float, u[i]), acc[i]);
+                for (int u = 0; u < UNROLL; ++u)
+                    if (c0 + u * kWave < chunks)
+                        v[u] = __builtin_nontemporal_load(src + (size_t)rows[j] * chunks + c0 + u * kWave);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    if (c0 + u * kWave < chunks) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const unsigned bits = v[u][i];  // a copy: bit_cast must not see the vector element itself
+                            if constexpr (BF16) {
+                                acc[u][2 * i] = fmaf(w[j], bf16_bits_to_float((unsigned short)(bits & 0xffffu)),
+                                                     acc[u][2 * i]);
+                                acc[u][2 * i + 1] = fmaf(w[j], bf16_bits_to_float((unsigned short)(bits >> 16)),
+                                                         acc[u][2 * i + 1]);
+                            } else {
+                                acc[u][i] = fmaf(w[j], __builtin_bit_cast(float, bits), acc[u][i]);
+                            }
+                        }
                     }
                 }
             }
         }
-        uint4 o;
-        if (BF16) {
-            o.x = (unsigned)float_to_bf16_bits(acc[0]) | ((unsigned)float_to_bf16_bits(acc[1]) << 16);
-            o.y = (unsigned)float_to_bf16_bits(acc[2]) | ((unsigned)float_to_bf16_bits(acc[3]) << 16);
-            o.z = (unsigned)float_to_bf16_bits(acc[4]) | ((unsigned)float_to_bf16_bits(acc[5]) << 16);
-            o.w = (unsigned)float_to_bf16_bits(acc[6]) | ((unsigned)float_to_bf16_bits(acc[7]) << 16);
-        } else {
-            o.x = __builtin_bit_cast(unsigned, acc[0]);
-            o.y = __builtin_bit_cast(unsigned, acc[1]);
-            o.z = __builtin_bit_cast(unsigned, acc[2]);
-            o.w = __builtin_bit_cast(unsigned, acc[3]);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            if (c0 + u * kWave < chunks) {
+                u32x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (BF16)
+                        o[i] = (unsigned)float_to_bf16_bits(acc[u][2 * i]) |
+                               ((unsigned)float_to_bf16_bits(acc[u][2 * i + 1]) << 16);
+                    else {
+                        const float a = acc[u][i];
+                        o[i] = __builtin_bit_cast(unsigned, a);
+                    }
+                }
+                __builtin_nontemporal_store(o, (u32x4*)out + (size_t)t * chunks + c0 + u * kWave);
+            }
         }
-        out[(size_t)t * chunks + c] = o;
     }
 }
 
@@ -79,11 +100,18 @@ extern "C" int moe_combine(const void* y_perm, int dtype, int T, int d, int k, c
     if (!y_perm || !row_of_assign || !topk_w || !out) return MOE_ERR_INVALID_ARG;
     const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == MOE_DTYPE_BF16)
-        hipLaunchKernelGGL((combine_kernel<true>), dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)y_perm,
-                           row_of_assign, topk_w, (uint4*)out, T, k, chunks);
-    else
-        hipLaunchKernelGGL((combine_kernel<false>), dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)y_perm,
-                           row_of_assign, topk_w, (uint4*)out, T, k, chunks);
+    // few experts per token: more pieces per lane to keep enough reads in flight
+    const bool wide = (k <= 4) && chunks >= 4 * kWave;
+    auto launch = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)y_perm, row_of_assign, topk_w,
+                           (uint4*)out, T, k, chunks);
+    };
+    if (dtype == MOE_DTYPE_BF16) {
+        if (wide) launch(combine_kernel<true, 4>);
+        else launch(combine_kernel<true, 1>);
+    } else {
+        if (wide) launch(combine_kernel<false, 4>);
+        else launch(combine_kernel<false, 1>);
+    }
     return check_launch();
 }

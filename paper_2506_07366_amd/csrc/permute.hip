@@ -321,23 +321,34 @@ __global__ __launch_bounds__(kPermThreads) void perm_place_kernel(int T, int k, 
 }
 
 // x_perm[row_of_assign[t*k + j], :] = x[t, :]: one wavefront per token, the row is
-// read once (16 bytes per lane per step) and stored to its k destinations
+// read once (16 bytes per lane per piece, UNROLL pieces in flight) and stored to its k
+// destinations.
+template <int UNROLL>
 __global__ __launch_bounds__(256) void perm_scatter_rows_kernel(const uint4* __restrict__ x,
                                                                  uint4* __restrict__ x_perm,
                                                                  const int32_t* __restrict__ row_of_assign, int T,
                                                                  int k, int chunks) {
+    typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
     const int lane = threadIdx.x & (kWave - 1);
     const int t = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
     if (t >= T) return;
     int rows[MOE_MAX_TOPK];
 #pragma unroll
     for (int j = 0; j < MOE_MAX_TOPK; ++j) rows[j] = j < k ? row_of_assign[(size_t)t * k + j] : 0;
-    const uint4* src = x + (size_t)t * chunks;
-    for (int c = lane; c < chunks; c += kWave) {
-        const uint4 v = src[c];
+    const u32x4* src = (const u32x4*)x + (size_t)t * chunks;
+    u32x4* dst = (u32x4*)x_perm;
+    for (int c0 = lane; c0 < chunks; c0 += kWave * UNROLL) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (c0 + u * kWave < chunks) v[u] = src[c0 + u * kWave];
 #pragma unroll
         for (int j = 0; j < MOE_MAX_TOPK; ++j)
-            if (j < k) x_perm[(size_t)rows[j] * chunks + c] = v;
+            if (j < k) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+                    if (c0 + u * kWave < chunks) dst[(size_t)rows[j] * chunks + c0 + u * kWave] = v[u];
+            }
     }
 }
 
@@ -399,8 +410,12 @@ extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int
         if ((rc = check_launch()) != MOE_OK) return rc;
         if (x_perm) {
             const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
-            hipLaunchKernelGGL(perm_scatter_rows_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)x,
-                               (uint4*)x_perm, row_of_assign, T, k, chunks);
+            auto launch = [&](auto kern) {
+                hipLaunchKernelGGL(kern, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)x, (uint4*)x_perm,
+                                   row_of_assign, T, k, chunks);
+            };
+            if (chunks >= 4 * kWave) launch(perm_scatter_rows_kernel<4>);
+            else launch(perm_scatter_rows_kernel<1>);
             if ((rc = check_launch()) != MOE_OK) return rc;
         }
     }
