@@ -371,6 +371,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                         }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                // The first fragments of the next k-tile were requested before the last
+                // step's MFMAs; they have landed by now.  Settling them here means no
+                // register that the LDS is still writing is live across the loop edge,
+                // where the compiler may place copies.
+                lds_wait<0>();
+                frags_landed(0);
             }
         };
         if (tm_valid == TM)
