@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--config", default="cfg2_mixtral_dist")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also print per-stage timings to stderr")
+    ap.add_argument("--fused-gather", action="store_true",
+                    help="time the variant that gathers token rows inside the first FFN product (no x_perm) "
+                         "as the main path; by default it is timed as an extra")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the G expert-parallel ranks are emulated as "
@@ -113,7 +116,7 @@ def main():
     Ws = wl.gen_weights_storage(cfg, threads=16)
     logits = torch.from_numpy(logits_h).cuda()
     x = to_device(wl.to_storage(x_h, cfg.dtype), cfg.dtype)
-    layer = MoELayer(cfg)
+    layer = MoELayer(cfg, fused_gather=args.fused_gather)
     layer.set_weights(*[to_device(w, cfg.dtype) for w in Ws])
 
     # predictions are inputs of the step: drawn on the host from the routing result
@@ -210,14 +213,29 @@ def main():
     hbm["combine_frac"] = hbm["combine_GBs"] / PEAK_HBM_GBS
     report = layer.load_report()
 
+    # the other row-gather variant, timed the same way (extra, not the headline)
+    other = MoELayer(cfg, fused_gather=not args.fused_gather)
+    other.packed = layer.packed
+    for _ in range(max(1, args.warmup)):
+        other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+    torch.cuda.synchronize()
+    other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    other_key = "six_call_path" if args.fused_gather else "fused_gather_path"
+
     result = {
         "metric": "MoE-layer tokens/s (route+plan+permute+FFN+combine); FFN MFMA % of peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed},
+        "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
+                   "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
         "stage_ms": stage_ms, "hbm_stages": hbm, "load": report,
+        other_key: {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, (logits_h, x_h, Ws, hist_pred_h, pred_idx_h, wl))

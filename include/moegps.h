@@ -176,7 +176,22 @@ int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, in
                     void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Optional timing hook for the next moe_grouped_ffn call on this host thread:
+ * Same FFN, but the activation rows are gathered inside the first product instead
+ * of being read from a permuted copy: row r of the (virtual) x_perm is
+ * x[assign_of_row[r] / k].  moe_permute can then be called with x_perm = NULL, which
+ * removes one write and one read of A*d elements from the layer.  Output and
+ * numerics are those of moe_grouped_ffn on the copied rows.
+ *   x [T, d] dtype in;  assign_of_row [T*k] int32 in (from moe_permute)
+ * The other arguments are those of moe_grouped_ffn with A = T*k.  T*d < 2^31.
+ */
+int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t* assign_of_row,
+                           int d, int ffn, int E,
+                           const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
+                           int seg_begin, int seg_end, const void* packed,
+                           void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Optional timing hook for the next moe_grouped_ffn / moe_grouped_ffn_gather call on this host thread:
  * events[0..3] are hipEvent_t handles (as void*) that the call records on its
  * stream before and after its first product (gate/up + SwiGLU) and before and
  * after its second product (down).  The hook is consumed by that one call.

@@ -24,7 +24,8 @@ MODE_NONE, MODE_DISTRIBUTION, MODE_TOKEN = 0, 1, 2
 EXPORTS = [
     "moe_strerror", "moe_last_hip_error", "moe_abi_version", "moe_route_topk", "moe_histogram",
     "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_packed_weights_bytes",
-    "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_time_next_call",
+    "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
+    "moe_grouped_ffn_time_next_call",
     "moe_combine",
 ]
 
@@ -74,6 +75,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn.restype = c_int
     lib.moe_grouped_ffn.argtypes = [vp, c_int, c_i64, c_int, c_int, c_int, vp, vp, c_int, c_int, c_int,
                                     vp, vp, vp, c_sz, vp]
+    lib.moe_grouped_ffn_gather.restype = c_int
+    lib.moe_grouped_ffn_gather.argtypes = [vp, c_int, c_int, c_int, vp, c_int, c_int, c_int, vp, vp, c_int, c_int,
+                                           c_int, vp, vp, vp, c_sz, vp]
     lib.moe_grouped_ffn_time_next_call.restype = c_int
     lib.moe_grouped_ffn_time_next_call.argtypes = [ctypes.POINTER(vp)]
     lib.moe_combine.restype = c_int
@@ -234,6 +238,33 @@ def moe_grouped_ffn(x_perm: torch.Tensor, seg_offsets: torch.Tensor, slot_expert
     _check(lib.moe_grouped_ffn(_ptr(x_perm), dt, A, d, ffn, E, _ptr(seg_offsets), _ptr(slot_expert), nseg,
                                seg_begin, seg_end, _ptr(packed), _ptr(y), _ptr(workspace), workspace.numel(),
                                _stream()), "moe_grouped_ffn")
+    return y
+
+
+def moe_grouped_ffn_gather(x: torch.Tensor, assign_of_row: torch.Tensor, k: int, seg_offsets: torch.Tensor,
+                           slot_expert: torch.Tensor, packed: torch.Tensor, E: int, ffn: int, seg_begin: int = 0,
+                           seg_end: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
+                           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """FFN with the row gather fused into the first product (no x_perm)."""
+    lib = load_library()
+    dt = dtype_code(x)
+    if not x.is_contiguous() or not x.is_cuda:
+        raise MoeGpsError("x must be a contiguous GPU tensor")
+    _need(assign_of_row, torch.int32, "assign_of_row")
+    _need(seg_offsets, torch.int32, "seg_offsets")
+    _need(slot_expert, torch.int32, "slot_expert")
+    T, d = x.shape
+    A = T * k
+    nseg = slot_expert.numel()
+    if seg_end is None:
+        seg_end = nseg
+    y = out if out is not None else torch.zeros((A, d), dtype=x.dtype, device=x.device)
+    need = moe_grouped_ffn_workspace_bytes(A, d, ffn, nseg, dt)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib.moe_grouped_ffn_gather(_ptr(x), dt, T, k, _ptr(assign_of_row), d, ffn, E, _ptr(seg_offsets),
+                                      _ptr(slot_expert), nseg, seg_begin, seg_end, _ptr(packed), _ptr(y),
+                                      _ptr(workspace), workspace.numel(), _stream()), "moe_grouped_ffn_gather")
     return y
 
 

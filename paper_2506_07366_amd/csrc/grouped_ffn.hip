@@ -170,7 +170,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
     const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
     bf16_t* __restrict__ C, int ldc,                 // output [rows, SWIGLU ? N/2 : N]
-    const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int N, int K, int group_n) {
+    const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int N, int K, int group_n,
+    const int32_t* __restrict__ gather_rows, int gather_div) {  // optional: A row r is A[gather_rows[r] / gather_div]
     constexpr int NW = WGM * WGN;
     constexpr int NT = NW * 64;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -226,7 +227,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         const int nt_i = grp * group_n + rem % gw;
         const MTile mt = mtiles[mt_i];
         const int n0 = nt_i * BN;
-        const bf16_t* Ab = A + (size_t)mt.row0 * lda;
+        // with a gather list the activation rows are fetched straight from their source
+        // (row gather_rows[r] / gather_div of A), otherwise from row r
+        const bf16_t* Ab = gather_rows ? A : A + (size_t)mt.row0 * lda;
         const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + (size_t)n0 * K;
         const int n_valid = (N - n0) < BN ? (N - n0) : BN;
 
@@ -238,7 +241,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         for (int i = 0; i < IAW; ++i) {
             const int p = (wave + i * NW) * 64 + lane;
             const int row = p / CPR, slot = p % CPR;
-            const int r = row < mt.rows ? row : mt.rows - 1;
+            int r = row < mt.rows ? row : mt.rows - 1;
+            if (gather_rows) r = gather_rows[mt.row0 + r] / gather_div;
             offA[i] = r * lda + ((slot ^ swz<CPR>(row)) * 8);
         }
 #pragma unroll
@@ -428,7 +432,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
                                                                 float* __restrict__ C, int ldc,
                                                                 const MTile* __restrict__ mtiles,
                                                                 const int32_t* __restrict__ n_mtiles_ptr, int N,
-                                                                int K) {
+                                                                int K, const int32_t* __restrict__ gather_rows,
+                                                                int gather_div) {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float sA[BK][BM + 4];
     __shared__ float sB1[BK][BN + 4];
@@ -448,7 +453,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
             for (int i = tid; i < BM * BK; i += 256) {
                 const int r = i / BK, c = i % BK;
                 const int rr = r < mt.rows ? r : mt.rows - 1;
-                sA[c][r] = (k0 + c < K) ? A[(size_t)(mt.row0 + rr) * lda + k0 + c] : 0.f;
+                const int src = gather_rows ? gather_rows[mt.row0 + rr] / gather_div : mt.row0 + rr;
+                sA[c][r] = (k0 + c < K) ? A[(size_t)src * lda + k0 + c] : 0.f;
             }
             for (int i = tid; i < BK * BN; i += 256) {
                 const int r = i / BN, c = i % BN;
@@ -526,7 +532,7 @@ struct GemmVariant {
     size_t lds;
     int threads;
     void (*kern)(const bf16_t*, int, const bf16_t*, size_t, bf16_t*, int, const MTile*, const int32_t*, int, int,
-                 int);
+                 int, const int32_t*, int);
 };
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
@@ -584,7 +590,7 @@ static int num_cus() {
 
 static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, const bf16_t* Bp, size_t b_stride,
                             bf16_t* C, int ldc, const MTile* tiles, const int32_t* n_tiles, int N, int K,
-                            int group_n, hipStream_t st) {
+                            int group_n, const int32_t* gather_rows, int gather_div, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute((const void*)v.kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds);
     if (e != hipSuccess) {
         set_last_hip_error(e);
@@ -592,7 +598,7 @@ static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, cons
     }
     // 32 workgroups for each of the 8 XCDs; the kernel walks the tile space itself
     hipLaunchKernelGGL(v.kern, dim3(kGemmGrid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles,
-                       n_tiles, N, K, group_n);
+                       n_tiles, N, K, group_n, gather_rows, gather_div);
     return check_launch();
 }
 
@@ -645,11 +651,12 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int
     return ffn_ws_layout(A, d, ffn, nseg, dtype, nullptr, nullptr);
 }
 
-extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
-                               const int32_t* seg_offsets, const int32_t* slot_expert, int nseg, int seg_begin,
-                               int seg_end, const void* packed, void* y_perm, void* workspace,
-                               size_t workspace_bytes, void* stream) {
-    using namespace moegps;
+namespace moegps {
+// x_perm rows are read directly (gather_rows == nullptr) or row r is x_perm[gather_rows[r] / gather_div]
+static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int gather_div, int dtype, int64_t A,
+                            int d, int ffn, int E, const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
+                            int seg_begin, int seg_end, const void* packed, void* y_perm, void* workspace,
+                            size_t workspace_bytes, void* stream) {
     if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
     if (A < 0 || d < 1 || ffn < 1 || E < 1 || nseg < 1) return MOE_ERR_INVALID_ARG;
     if (seg_begin < 0 || seg_end > nseg || seg_begin > seg_end) return MOE_ERR_INVALID_ARG;
@@ -676,11 +683,11 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
         const float* w2 = w3 + per;
         const int grid = 4 * num_cus();
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), dim3(grid), dim3(256), 0, st, (const float*)x_perm, d, w1,
-                           w3, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts, ffn, d);
+                           w3, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts, ffn, d, gather_rows, gather_div);
         if ((rc = check_launch()) != MOE_OK) return rc;
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), dim3(grid), dim3(256), 0, st, (const float*)ws.h, ffn,
                            w2, (const float*)nullptr, (size_t)d * ffn, (float*)y_perm, d, ws.tiles1, ws.counts, d,
-                           ffn);
+                           ffn, (const int32_t*)nullptr, 1);
         return check_launch();
     }
 
@@ -709,14 +716,34 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
     rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)2 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
-                          ws.counts, 2 * ffn, d, group_n, st);
+                          ws.counts, 2 * ffn, d, group_n, gather_rows, gather_div, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
     rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, tiles2, count2,
-                          d, ffn, group_n, st);
+                          d, ffn, group_n, nullptr, 1, st);
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
+}
+}  // namespace moegps
+
+extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
+                               const int32_t* seg_offsets, const int32_t* slot_expert, int nseg, int seg_begin,
+                               int seg_end, const void* packed, void* y_perm, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    return moegps::grouped_ffn_impl(x_perm, nullptr, 1, dtype, A, d, ffn, E, seg_offsets, slot_expert, nseg, seg_begin,
+                                    seg_end, packed, y_perm, workspace, workspace_bytes, stream);
+}
+
+extern "C" int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t* assign_of_row, int d,
+                                      int ffn, int E, const int32_t* seg_offsets, const int32_t* slot_expert,
+                                      int nseg, int seg_begin, int seg_end, const void* packed, void* y_perm,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || k < 1 || d < 1) return MOE_ERR_INVALID_ARG;
+    if ((int64_t)T * d >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit element offsets into x
+    if (T > 0 && !assign_of_row) return MOE_ERR_INVALID_ARG;
+    return moegps::grouped_ffn_impl(x, assign_of_row, k, dtype, (int64_t)T * k, d, ffn, E, seg_offsets, slot_expert,
+                                    nseg, seg_begin, seg_end, packed, y_perm, workspace, workspace_bytes, stream);
 }
 
 extern "C" int moe_grouped_ffn_time_next_call(void* const* events) {

@@ -29,8 +29,11 @@ def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
 
 
 class MoELayer:
-    def __init__(self, cfg: MoEConfig, device="cuda"):
+    def __init__(self, cfg: MoEConfig, device="cuda", fused_gather: bool = False):
+        """fused_gather: gather the token rows inside the first FFN product
+        (moe_grouped_ffn_gather) instead of materialising x_perm in moe_permute."""
         self.cfg = cfg
+        self.fused_gather = fused_gather
         self.dev = torch.device(device)
         c = cfg
         dt = torch_dtype(c)
@@ -47,7 +50,7 @@ class MoELayer:
             seg_offsets=torch.empty(c.nseg + 1, **i32),
             row_of_assign=torch.empty(c.A, **i32),
             assign_of_row=torch.empty(c.A, **i32),
-            x_perm=torch.empty((c.A, c.d), dtype=dt, device=self.dev),
+            x_perm=None if fused_gather else torch.empty((c.A, c.d), dtype=dt, device=self.dev),
             rank_load=torch.empty(c.G, **i32),
         )
         self.y_perm = torch.zeros((c.A, c.d), dtype=dt, device=self.dev)
@@ -90,6 +93,7 @@ class MoELayer:
 
     def permute(self, mode, x, pred_idx):
         c = self.cfg
+        self._x = x
         B.moe_permute(mode, x, self.topk_idx, pred_idx if mode == MODE_TOKEN else None, self.hist, self._hp,
                       self.slot_expert, self.slot_quota, c.E, c.G, c.S, workspace=self.ws_perm, out=self.perm)
 
@@ -97,8 +101,13 @@ class MoELayer:
         c = self.cfg
         if self.packed is None:
             raise B.MoeGpsError("set_weights() first")
-        B.moe_grouped_ffn(self.perm["x_perm"], self.perm["seg_offsets"], self.slot_expert, self.packed, c.E, c.ffn,
-                          seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm)
+        if self.fused_gather:
+            B.moe_grouped_ffn_gather(self._x, self.perm["assign_of_row"], c.k, self.perm["seg_offsets"],
+                                     self.slot_expert, self.packed, c.E, c.ffn, seg_begin, seg_end,
+                                     workspace=self.ws_ffn, out=self.y_perm)
+        else:
+            B.moe_grouped_ffn(self.perm["x_perm"], self.perm["seg_offsets"], self.slot_expert, self.packed, c.E,
+                              c.ffn, seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm)
 
     def combine(self):
         c = self.cfg

@@ -195,3 +195,46 @@ def test_identity_round_trip_permute_combine():
                         dev_i32(case.plan.slot_quota), cfg.E, cfg.G, cfg.S)
     back = B.moe_combine(out["x_perm"], out["row_of_assign"], w, cfg.T, cfg.k)
     assert np.max(np.abs(to_host_f32(back) - case.x)) <= 1e-5 * np.max(np.abs(case.x))
+
+
+@pytest.mark.parametrize("name,mode", [("cfg1_tiny_f32", 1), ("mid_bf16", 0), ("mid_bf16", 1), ("mid_bf16", 2),
+                                       ("cfg4_finegrained", 1)])
+def test_fused_gather_equals_copied_rows(name, mode):
+    """Gathering the token rows inside the first product must give exactly what the
+    FFN gives on the copied rows (same arithmetic on the same values)."""
+    cfg = wl.CONFIGS[name].replace(mode=mode, acc=0.9)
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    dw = dev_weights(cfg, Ws)
+    outs = []
+    for fused in (False, True):
+        layer = MoELayer(cfg, fused_gather=fused)
+        layer.set_weights(*dw)
+        out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(),
+                         pred_idx=case.dev_pred_idx())
+        torch.cuda.synchronize()
+        outs.append((layer.y_perm.float().cpu().numpy().copy(), out.float().cpu().numpy().copy()))
+        assert np.array_equal(layer.perm["row_of_assign"].cpu().numpy(), case.perm["row_of_assign"])
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_fused_gather_slot_range_and_oracle():
+    cfg = wl.CONFIGS["mid_bf16"]
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    Wf = [wl.from_storage(w, cfg.dtype) for w in Ws]
+    layer = MoELayer(cfg, fused_gather=True)
+    layer.set_weights(*dev_weights(cfg, Ws))
+    layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=None)
+    x_perm = case.x[case.perm["assign_of_row"] // cfg.k]
+    ref = grouped_ffn(x_perm, case.perm["seg_offsets"], case.plan.slot_expert, *Wf)
+    assert rel_err(to_host_f32(layer.y_perm), ref) <= TOL["bf16"]
+    # one rank's slots alone
+    layer.y_perm.zero_()
+    layer.ffn(seg_begin=cfg.S, seg_end=2 * cfg.S)
+    so = case.perm["seg_offsets"]
+    got = to_host_f32(layer.y_perm)
+    lo, hi = so[cfg.S], so[2 * cfg.S]
+    assert rel_err(got[lo:hi], ref[lo:hi]) <= TOL["bf16"]
+    assert np.all(got[:lo] == 0) and np.all(got[hi:] == 0)
