@@ -34,7 +34,7 @@ def describe(cfg):
             f"G={cfg.G}x{cfg.S} slots, {mode} plan")
 
 
-def cpu_baseline(cfg, case_inputs, max_rows=1024):
+def cpu_baseline(cfg, case_inputs, max_rows=4096):
     """Time the oracle on the host: integer stages in full, the fp64 FFN + combine on
     whole segments holding at most ``max_rows`` rows, scaled linearly to all rows."""
     import oracle
@@ -213,6 +213,33 @@ def main():
     hbm["combine_frac"] = hbm["combine_GBs"] / PEAK_HBM_GBS
     report = layer.load_report()
 
+    # each virtual rank's share of the FFN alone (its S slots), with and without the
+    # duplication plan: the bottleneck rank is what expert parallelism would wait for
+    def rank_ffn_ms(lay, reps=3):
+        out = []
+        for g in range(cfg.G):
+            s_, e_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            lay.ffn(g * cfg.S, (g + 1) * cfg.S)
+            s_.record()
+            for _ in range(reps):
+                lay.ffn(g * cfg.S, (g + 1) * cfg.S)
+            e_.record()
+            torch.cuda.synchronize()
+            out.append(s_.elapsed_time(e_) / reps)
+        return out
+
+    ranks = {"mode": cfg.mode, "ffn_ms": rank_ffn_ms(layer)}
+    ranks["makespan_ms"] = max(ranks["ffn_ms"])
+    if cfg.mode != 0:
+        home = MoELayer(cfg, fused_gather=args.fused_gather)
+        home.packed = layer.packed
+        home.step(logits, x, mode=0)
+        torch.cuda.synchronize()
+        t_home = rank_ffn_ms(home)
+        ranks["no_duplication"] = {"ffn_ms": t_home, "makespan_ms": max(t_home),
+                                   "rank_load": home.load_report()["rank_load"]}
+        del home
+
     # the other row-gather variant, timed the same way (extra, not the headline)
     other = MoELayer(cfg, fused_gather=not args.fused_gather)
     other.packed = layer.packed
@@ -234,7 +261,7 @@ def main():
         "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
-        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report,
+        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks,
         other_key: {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"},
     }
     if not args.no_cpu_baseline:
