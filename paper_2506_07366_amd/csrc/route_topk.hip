@@ -1,21 +1,49 @@
 // Gate top-k: the token->expert map f of Algorithm 1 (Background: tokens are
 // routed to their top-K experts).  A group of LPT lanes of a 64-wide wavefront
 // owns one token; every lane keeps VPL logits in registers and the k winners are
-// found by k rounds of a cross-lane butterfly arg-max.  Order is (logit
+// found by k rounds of a cross-lane arg-max (DPP lane permutes inside a row of 16).  Order is (logit
 // descending, expert index ascending), so equal logits go to the lowest index.
 // Gate weights are a softmax over the k selected logits.
 #include "common.h"
 
 namespace moegps {
 
-struct Cand {
-    float v;
-    int e;
-};
+// true if (bv, be) comes before (av, ae) in (value descending, index ascending) order
+__device__ __forceinline__ bool better(float bv, int be, float av, int ae) {
+    return (bv > av) || (bv == av && be < ae);
+}
 
-// true if b comes before a in (value descending, index ascending) order
-__device__ __forceinline__ bool better(const Cand& b, const Cand& a) {
-    return (b.v > a.v) || (b.v == a.v && b.e < a.e);
+// One butterfly level with a lane permute that stays inside the vector ALU (no LDS
+// crossbar): every lane keeps the better of its own candidate and its partner's.
+template <int CTRL>
+__device__ __forceinline__ void dpp_level(float& v, int& e) {
+    const float ov =
+        __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+    const int oe = __builtin_amdgcn_update_dpp(0, e, CTRL, 0xf, 0xf, false);
+    const bool take = better(ov, oe, v, e);
+    v = take ? ov : v;
+    e = take ? oe : e;
+}
+template <int MASK>
+__device__ __forceinline__ void shfl_level(float& v, int& e) {
+    const float ov = __shfl_xor(v, MASK, kWave);
+    const int oe = __shfl_xor(e, MASK, kWave);
+    const bool take = better(ov, oe, v, e);
+    v = take ? ov : v;
+    e = take ? oe : e;
+}
+
+// Best candidate of each group of LPT consecutive lanes, known to all its lanes.
+// Inside a row of 16 lanes: quad permutes, then the half-row and row mirrors; across
+// rows one or two shuffles.
+template <int LPT>
+__device__ __forceinline__ void group_best(float& v, int& e) {
+    if constexpr (LPT >= 2) dpp_level<0xB1>(v, e);    // quad_perm [1,0,3,2]
+    if constexpr (LPT >= 4) dpp_level<0x4E>(v, e);    // quad_perm [2,3,0,1]
+    if constexpr (LPT >= 8) dpp_level<0x141>(v, e);   // row_half_mirror
+    if constexpr (LPT >= 16) dpp_level<0x140>(v, e);  // row_mirror
+    if constexpr (LPT >= 32) shfl_level<16>(v, e);
+    if constexpr (LPT == 64) shfl_level<32>(v, e);
 }
 
 template <int LPT, int VPL>
@@ -44,27 +72,24 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     for (int j = 0; j < k; ++j) {
         // best remaining candidate of this lane; padding columns carry their own
         // (out of range) index and so lose every tie against a real expert
-        Cand best{NEG_INF, 0x7fffffff};
+        float bv = NEG_INF;
+        int be = 0x7fffffff;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
-            Cand c{v[i], sub + i * LPT};
-            if (!((taken >> i) & 1u) && better(c, best)) best = c;
+            const int ce = sub + i * LPT;
+            const bool take = !((taken >> i) & 1u) && better(v[i], ce, bv, be);
+            bv = take ? v[i] : bv;
+            be = take ? ce : be;
         }
-#pragma unroll
-        for (int m = 1; m < LPT; m <<= 1) {
-            Cand o;
-            o.v = __shfl_xor(best.v, m, kWave);
-            o.e = __shfl_xor(best.e, m, kWave);
-            if (better(o, best)) best = o;
-        }
+        group_best<LPT>(bv, be);
         // the owner retires the winner
-        if ((best.e % LPT) == sub) taken |= 1u << (best.e / LPT);
-        if (j == 0) l0 = best.v;
-        const float ex = expf(best.v - l0);
+        if ((be % LPT) == sub) taken |= 1u << (be / LPT);
+        if (j == 0) l0 = bv;
+        const float ex = expf(bv - l0);
         sum += ex;
         if (sub == j) {
             my_ex = ex;
-            my_e = best.e;
+            my_e = be;
         }
     }
     if (live && sub < k) {
