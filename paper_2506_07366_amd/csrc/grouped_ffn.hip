@@ -69,49 +69,69 @@ __global__ void copy_u4_kernel(const uint4* __restrict__ in, uint4* __restrict__
 // ---------------------------------------------------------------------------
 // M-tile table from the ragged segments
 // ---------------------------------------------------------------------------
+// Order of the table: first every full-height tile, by (expert, segment), so that
+// neighbours mostly read the same expert's weights; then the ragged last tile of
+// every segment, tallest first.  Workgroups claim tiles in table order, so the cheap
+// tiles come last and fill the gaps at the end of the launch.
+// n_tiles[0] = number of tiles, n_tiles[1] = number of full-height tiles; `queues`
+// (the claim counters of the launches that walk the table) is cleared here.
 __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __restrict__ seg_offsets,
                                                              const int32_t* __restrict__ slot_expert, int seg_begin,
                                                              int seg_end, int E, int BM, MTile* __restrict__ tiles,
-                                                             int capacity, int32_t* __restrict__ n_tiles) {
-    // Tiles are listed by (expert, segment): tiles that are neighbours in the table
-    // mostly read the same expert's weights.
-    __shared__ int cnt[MOE_MAX_SEGMENTS];
+                                                             int capacity, int32_t* __restrict__ n_tiles,
+                                                             int32_t* __restrict__ queues, int n_queues) {
+    __shared__ int nfull[MOE_MAX_SEGMENTS];  // full-height tiles of the segment
+    __shared__ int tail[MOE_MAX_SEGMENTS];   // rows of its ragged last tile (0: none)
     __shared__ int ex[MOE_MAX_SEGMENTS];
-    __shared__ int total_s;
+    __shared__ int total_full, total_tail;
     const int ns = seg_end - seg_begin;
-    if (threadIdx.x == 0) total_s = 0;
+    if (threadIdx.x == 0) total_full = total_tail = 0;
+    for (int i = threadIdx.x; i < n_queues; i += blockDim.x) queues[i] = 0;
     __syncthreads();
     for (int i = threadIdx.x; i < ns; i += blockDim.x) {
         const int s = seg_begin + i;
         const int rows = seg_offsets[s + 1] - seg_offsets[s];
         const int e = slot_expert[s];
-        const int c = (rows > 0 && e >= 0 && e < E) ? (rows + BM - 1) / BM : 0;
-        cnt[i] = c;
+        const bool live = rows > 0 && e >= 0 && e < E;
+        nfull[i] = live ? rows / BM : 0;
+        tail[i] = live ? rows % BM : 0;
         ex[i] = e;
-        if (c) atomicAdd(&total_s, c);
+        if (nfull[i]) atomicAdd(&total_full, nfull[i]);
+        if (tail[i]) atomicAdd(&total_tail, 1);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < ns; i += blockDim.x) {
-        const int nt = cnt[i];
-        if (nt == 0) continue;
-        int base = 0;
-        for (int j = 0; j < ns; ++j)
-            if (ex[j] < ex[i] || (ex[j] == ex[i] && j < i)) base += cnt[j];
+        const int nf = nfull[i], tl = tail[i];
+        if (nf == 0 && tl == 0) continue;
+        int base = 0, rank = 0;
+        for (int j = 0; j < ns; ++j) {
+            const bool before = ex[j] < ex[i] || (ex[j] == ex[i] && j < i);
+            if (before) base += nfull[j];
+            if (tail[j] > tl || (tail[j] == tl && before)) ++rank;  // tail[j] > 0 whenever tl > 0 reaches here
+        }
         const int s = seg_begin + i;
-        const int lo = seg_offsets[s], hi = seg_offsets[s + 1];
-        for (int t = 0; t < nt; ++t) {
-            const int slot = base + t;
-            if (slot < capacity) {
-                MTile mt;
+        const int lo = seg_offsets[s];
+        MTile mt;
+        mt.expert = ex[i];
+        mt.seg = s;
+        for (int t = 0; t < nf; ++t) {
+            if (base + t < capacity) {
                 mt.row0 = lo + t * BM;
-                mt.rows = (hi - mt.row0) < BM ? (hi - mt.row0) : BM;
-                mt.expert = ex[i];
-                mt.seg = s;
-                tiles[slot] = mt;
+                mt.rows = BM;
+                tiles[base + t] = mt;
             }
         }
+        if (tl > 0 && total_full + rank < capacity) {
+            mt.row0 = lo + nf * BM;
+            mt.rows = tl;
+            tiles[total_full + rank] = mt;
+        }
     }
-    if (threadIdx.x == 0) n_tiles[0] = total_s < capacity ? total_s : capacity;
+    if (threadIdx.x == 0) {
+        const int all = total_full + total_tail;
+        n_tiles[0] = all < capacity ? all : capacity;
+        n_tiles[1] = total_full < capacity ? total_full : capacity;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -170,7 +190,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
     const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
     bf16_t* __restrict__ C, int ldc,                 // output [rows, SWIGLU ? N/2 : N]
-    const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int N, int K, int group_n,
+    const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int32_t* __restrict__ queues,
+    int N, int K, int group_n,
     const int32_t* __restrict__ gather_rows, int gather_div) {  // optional: A row r is A[gather_rows[r] / gather_div]
     constexpr int NW = WGM * WGN;
     constexpr int NT = NW * 64;
@@ -202,28 +223,69 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const int l32 = lane & 31, half = lane >> 5;
 
     const int n_mtiles = n_mtiles_ptr[0];
+    const int n_full = n_mtiles_ptr[1];  // the table lists these full-height tiles first
     const int n_ntiles = (N + BN - 1) / BN;
     const int KT = K / BK;
 
-    // Tile order.  Tiles are numbered in groups of group_n neighbouring N-tiles; inside
-    // a group the N-tile index runs fastest, then the M-tile (M-tiles are sorted by
-    // expert), so 32 consecutive tiles form a patch of about 32/group_n x group_n tiles
-    // that share their activation and weight panels.  Workgroups are dealt to the 8 XCDs
-    // round-robin (workgroup b runs on XCD b % 8) and every XCD has its own L2, so the
-    // 32 workgroups of one XCD take one such run of 32 consecutive tiles at a time and
-    // share its panels through that L2; the 8 XCDs take 8 consecutive runs (further
-    // along M under the same weight panels, shared through the memory-side cache).
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int per_xcd = (int)(gridDim.x >> 3);
+    // Tile order.  The (M-tile, N-tile) space is walked in two passes, the full-height
+    // M-tiles first and the ragged ones (tallest first) after them.  Inside a pass tiles
+    // are numbered in groups of group_n neighbouring N-tiles; inside a group the N-tile
+    // index runs fastest, then the M-tile (full M-tiles are sorted by expert), so a run of
+    // 32 consecutive tiles is a patch of about 32/group_n x group_n tiles that share their
+    // activation and weight panels.  Workgroups are dealt to the 8 XCDs round-robin
+    // (workgroup b runs on XCD b % 8) and every XCD has its own L2, so run c of the
+    // numbering belongs to XCD c % 8: its workgroups claim the tiles of its runs one by
+    // one from a counter (tiles differ in cost, a fixed deal would leave workgroups idle
+    // at the end) and so work side by side on one patch, sharing its panels through that
+    // L2; the 8 XCDs are on 8 consecutive runs (further along M under the same weight
+    // panels, shared through the memory-side cache).  A workgroup whose own XCD has no
+    // tile left claims from the other XCDs' counters.
+    const int xcd = blockIdx.x & 7;
+    const int run = (int)(gridDim.x >> 3);
     const int total = n_mtiles * n_ntiles;
-    const int per_group = n_mtiles * group_n;
-    for (int chunk = xcd; chunk * per_xcd < total; chunk += 8) {
-        const int t = chunk * per_xcd + slot;
-        if (t >= total) continue;  // uniform over the workgroup
+    const int total_full = n_full * n_ntiles;
+    __shared__ volatile int next_tile;
+    int q_done = 0;  // thread 0: counters xcd .. xcd + q_done - 1 (mod 8) have run out
+    // tile number for claim i of XCD q's counter, -1 if that counter has run out
+    auto tile_of_claim = [&](int q, int i) {
+        const int t = (q + 8 * (i / run)) * run + i % run;
+        return t < total ? t : -1;  // claims only grow: past the end once, past the end for good
+    };
+    // thread 0 only: turns a claim made ahead of time (or none: q < 0) into a tile, making
+    // further claims as needed; -1 when every counter has run out
+    auto settle_claim = [&](int q, int i) {
+        for (;;) {
+            if (q >= 0) {
+                const int t = tile_of_claim(q, i);
+                if (t >= 0) return t;
+                if (q == ((xcd + q_done) & 7)) ++q_done;
+            }
+            if (q_done >= 8) return -1;
+            q = (xcd + q_done) & 7;
+            i = atomicAdd(&queues[q], 1);
+        }
+    };
+    if (tid == 0) next_tile = settle_claim(-1, 0);
+    for (;;) {
+        lds_wait<0>();                 // thread 0's store of next_tile
+        __builtin_amdgcn_s_barrier();  // also: every wavefront is done reading the previous tile's stages
+        const int t_all = __builtin_amdgcn_readfirstlane(next_tile);
+        if (t_all < 0) break;
+        // the claim for the tile after this one is made now and looked at after the K loop
+        int ahead_q = -1, ahead_i = 0;
+        if (tid == 0 && q_done < 8) {
+            ahead_q = (xcd + q_done) & 7;
+            ahead_i = atomicAdd(&queues[ahead_q], 1);
+        }
+        const bool ragged_pass = t_all >= total_full;
+        const int t = ragged_pass ? t_all - total_full : t_all;
+        const int m_base = ragged_pass ? n_full : 0;
+        const int m_count = ragged_pass ? n_mtiles - n_full : n_full;
+        const int per_group = m_count * group_n;
         const int grp = t / per_group;
         const int rem = t - grp * per_group;
         const int gw = (n_ntiles - grp * group_n) < group_n ? (n_ntiles - grp * group_n) : group_n;
-        const int mt_i = rem / gw;
+        const int mt_i = m_base + rem / gw;
         const int nt_i = grp * group_n + rem % gw;
         const MTile mt = mtiles[mt_i];
         const int n0 = nt_i * BN;
@@ -283,7 +345,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        __builtin_amdgcn_s_barrier();  // every wavefront is done reading the previous tile's stages
 #pragma unroll
         for (int s = 0; s < NSTAGE; ++s)
             if (s < KT) issue_loads(s, s);
@@ -387,6 +448,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             k_loop(std::true_type{});
         else
             k_loop(std::false_type{});
+        // every wavefront has read next_tile (the K loop holds a barrier)
+        if (tid == 0) next_tile = settle_claim(ahead_q, ahead_i);
 
         // epilogue: 4 consecutive columns per lane and accumulator group -> 8-byte stores
         const int col_w = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN)) + half * 4;
@@ -503,7 +566,8 @@ struct FfnWs {
     void* h;          // [A, ffn] hidden activations
     MTile* tiles1;    // M-tiles for GEMM-1
     MTile* tiles2;    // M-tiles for GEMM-2
-    int32_t* counts;  // [2] number of M-tiles
+    int32_t* counts;  // [0..1], [2..3]: number of M-tiles and of full-height M-tiles in tiles1, tiles2
+    int32_t* queues;  // [0..7], [8..15]: per-XCD claim counters of GEMM-1, GEMM-2
     int capacity;
 };
 
@@ -523,6 +587,7 @@ static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char
     w.tiles1 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.tiles2 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.counts = (int32_t*)take(256);
+    w.queues = w.counts ? w.counts + 8 : nullptr;
     if (ws) *ws = w;
     return off;
 }
@@ -531,8 +596,8 @@ struct GemmVariant {
     int bm, bn;
     size_t lds;
     int threads;
-    void (*kern)(const bf16_t*, int, const bf16_t*, size_t, bf16_t*, int, const MTile*, const int32_t*, int, int,
-                 int, const int32_t*, int);
+    void (*kern)(const bf16_t*, int, const bf16_t*, size_t, bf16_t*, int, const MTile*, const int32_t*, int32_t*, int,
+                 int, int, const int32_t*, int);
 };
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
@@ -589,16 +654,16 @@ static int num_cus() {
 }
 
 static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, const bf16_t* Bp, size_t b_stride,
-                            bf16_t* C, int ldc, const MTile* tiles, const int32_t* n_tiles, int N, int K,
-                            int group_n, const int32_t* gather_rows, int gather_div, hipStream_t st) {
+                            bf16_t* C, int ldc, const MTile* tiles, const int32_t* n_tiles, int32_t* queues, int N,
+                            int K, int group_n, const int32_t* gather_rows, int gather_div, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute((const void*)v.kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds);
     if (e != hipSuccess) {
         set_last_hip_error(e);
         return MOE_ERR_HIP;
     }
-    // 32 workgroups for each of the 8 XCDs; the kernel walks the tile space itself
+    // 32 workgroups for each of the 8 XCDs; they claim tiles from `queues` (cleared by the table builder)
     hipLaunchKernelGGL(v.kern, dim3(kGemmGrid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles,
-                       n_tiles, N, K, group_n, gather_rows, gather_div);
+                       n_tiles, queues, N, K, group_n, gather_rows, gather_div);
     return check_launch();
 }
 
@@ -676,7 +741,7 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
 
     if (dtype == MOE_DTYPE_F32) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
-                           seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts);
+                           seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts, (int32_t*)nullptr, 0);
         if ((rc = check_launch()) != MOE_OK) return rc;
         const float* w1 = (const float*)packed;
         const float* w3 = w1 + per;
@@ -699,16 +764,16 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
     const GemmVariant& g1 = kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
-                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts);
+                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16);
     if ((rc = check_launch()) != MOE_OK) return rc;
     const MTile* tiles2 = ws.tiles1;
     const int32_t* count2 = ws.counts;
     if (g2.bm != g1.bm) {  // the second product walks its own M-tiles only if its tile height differs
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
-                           seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 1);
+                           seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 2, (int32_t*)nullptr, 0);
         if ((rc = check_launch()) != MOE_OK) return rc;
         tiles2 = ws.tiles2;
-        count2 = ws.counts + 1;
+        count2 = ws.counts + 2;
     }
     const bf16_t* p13 = (const bf16_t*)packed;
     const bf16_t* p2 = p13 + 2 * per;
@@ -716,12 +781,12 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
     rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)2 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
-                          ws.counts, 2 * ffn, d, group_n, gather_rows, gather_div, st);
+                          ws.counts, ws.queues, 2 * ffn, d, group_n, gather_rows, gather_div, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
     rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, tiles2, count2,
-                          d, ffn, group_n, nullptr, 1, st);
+                          ws.queues + 8, d, ffn, group_n, nullptr, 1, st);
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
 }
