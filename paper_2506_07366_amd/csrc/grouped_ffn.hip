@@ -759,8 +759,14 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
     int v1 = env_int("MOEGPS_FFN_TILE1", 3), v2 = env_int("MOEGPS_FFN_TILE2", 3);
     if (v1 < 0 || v1 >= kNumVariants) v1 = 0;
     if (v2 < 0 || v2 >= kNumVariants) v2 = 0;
-    int group_n = env_int("MOEGPS_FFN_GROUP_N", 8);
-    if (group_n < 1) group_n = 1;
+    // N-tiles walked side by side under one run of M-tiles: all of them when the output is
+    // narrow (at most 16 tiles), else 8 (measured best on the Mixtral-shaped gate/up product)
+    const int group_env = env_int("MOEGPS_FFN_GROUP_N", 0);
+    auto group_for = [&](int n_cols, int bn) {
+        if (group_env > 0) return group_env;
+        const int n_ntiles = ceil_div(n_cols, bn);
+        return n_ntiles <= 16 ? n_ntiles : 8;
+    };
     const GemmVariant& g1 = kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
@@ -781,12 +787,12 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
     rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)2 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
-                          ws.counts, ws.queues, 2 * ffn, d, group_n, gather_rows, gather_div, st);
+                          ws.counts, ws.queues, 2 * ffn, d, group_for(2 * ffn, g1.bn), gather_rows, gather_div, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
     rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, tiles2, count2,
-                          ws.queues + 8, d, ffn, group_n, nullptr, 1, st);
+                          ws.queues + 8, d, ffn, group_for(d, g2.bn), nullptr, 1, st);
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
 }
