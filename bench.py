@@ -27,6 +27,27 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_F32_TFLOPS = 157.3     # MI355X fp32 vector peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# Bytes moved between the L2s and memory by one launch of the gate/up product, from hardware
+# counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter
+# reads for the library's plain copy kernel; summary under profiles/).  The figures belong to
+# one version of the kernel source: they are reported only while its digest still matches.
+KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
+                             "grouped_ffn.hip")
+TRAFFIC = {
+    "cfg2_mixtral_dist": {"source_sha256": "", "fetch_bytes": 0, "write_bytes": 0},
+}
+
+
+def measured_traffic(config_name):
+    import hashlib
+    rec = TRAFFIC.get(config_name)
+    if not rec or not rec["source_sha256"] or not os.path.exists(KERNEL_SOURCE):
+        return None
+    with open(KERNEL_SOURCE, "rb") as f:
+        if hashlib.sha256(f.read()).hexdigest() != rec["source_sha256"]:
+            return None
+    return rec["fetch_bytes"] + rec["write_bytes"]
+
 
 def describe(cfg):
     mode = {0: "no prediction", 1: "distribution-only", 2: "token-to-expert"}[cfg.mode]
@@ -93,6 +114,9 @@ def main():
     ap.add_argument("--fused-gather", action="store_true",
                     help="time the variant that gathers token rows inside the first FFN product (no x_perm) "
                          "as the main path; by default it is timed as an extra")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch the library's plain copy kernel on 256 MiB buffers (three launches), so that a "
+                         "hardware-counter run of this command holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the G expert-parallel ranks are emulated as "
@@ -111,6 +135,13 @@ def main():
 
     cfg = wl.CONFIGS[args.config]
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        # fp32 "packing" is three launches of copy_u4_kernel, each reading and writing E*d*ffn*4 bytes
+        w = torch.ones((1, 8192, 8192), dtype=torch.float32, device="cuda")
+        w2 = torch.ones((1, 8192, 8192), dtype=torch.float32, device="cuda")
+        B.moe_pack_weights(w, w, w2)
+        torch.cuda.synchronize()
+        del w, w2
     logits_h = wl.gen_logits(cfg)
     x_h = wl.gen_x(cfg)
     Ws = wl.gen_weights_storage(cfg, threads=16)
@@ -166,7 +197,7 @@ def main():
         achieved = flops1 / (g1_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<swiglu> (gate/up product)",
                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "avg_ms": g1_ms,
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config), "avg_ms": g1_ms,
                     "down_product": {"avg_ms": g2_ms, "achieved": flops2 / (g2_ms * 1e-3) / 1e12,
                                      "frac": flops2 / (g2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
                     "ffn_frac_of_peak": (flops1 + flops2) / ((g1_ms + g2_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
