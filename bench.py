@@ -271,6 +271,14 @@ def main():
                                    "rank_load": home.load_report()["rank_load"]}
         del home
 
+    # rows that would cross the emulated ranks at dispatch and combine (one extra C-ABI call,
+    # outside the timed region), with its own kernel time
+    comm = layer.comm_report(cfg.mode, pred_idx)
+    time_stage("comm_matrix", lambda: B.moe_comm_matrix(cfg.mode, layer.topk_idx, pred_idx if cfg.mode == 2 else None,
+                                                        layer.perm["row_of_assign"], layer.perm["seg_offsets"],
+                                                        cfg.G, cfg.S))
+    comm["kernel_ms"] = stage_ms.pop("comm_matrix")
+
     # the other row-gather variant, timed the same way (extra, not the headline)
     other = MoELayer(cfg, fused_gather=not args.fused_gather)
     other.packed = layer.packed
@@ -292,7 +300,7 @@ def main():
         "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
-        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks,
+        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
         other_key: {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"},
     }
     if not args.no_cpu_baseline:

@@ -209,6 +209,29 @@ int moe_grouped_ffn_time_next_call(void* const* events);
 int moe_combine(const void* y_perm, int dtype, int T, int d, int k,
                 const int32_t* row_of_assign, const float* topk_w, void* out, void* stream);
 
+/*
+ * Rows that cross the emulated expert-parallel ranks (Background, "Routing incurs
+ * inter-device communication": with N ranks and a balanced distribution (N-1)/N of a
+ * rank's rows leave it and the rank of the most popular expert receives skewness times
+ * the average; the all-to-all after the FFN moves the same rows back.  Section 3.2.2:
+ * under Token-to-Expert prediction a correctly predicted token is already on the rank of
+ * its expert; Section 3.3: a mispredicted one still has to be moved).
+ * Token t is owned by rank floor(t*G/T).  For every assignment a = t*k + j, with
+ * dst = rank of the segment that holds row_of_assign[a]:
+ *     dispatch[src*G + dst] += 1   src = owner(t), or dst when mode is MOE_MODE_TOKEN and
+ *                                  topk_idx[a] is among pred_idx[t, 0..k)
+ *     combine[dst*G + owner(t)] += 1
+ *   topk_idx [T, k], pred_idx [T, k] (MOE_MODE_TOKEN only, else may be NULL),
+ *   row_of_assign [A], seg_offsets [G*S + 1] (outputs of moe_permute): device in;
+ *   dispatch, combine [G, G] int32: device out, overwritten (all zero when T = 0).
+ * Limits as for moe_permute.  Returns MOE_ERR_INVALID_ARG / MOE_ERR_UNSUPPORTED before
+ * any launch when an argument is out of range.
+ */
+int moe_comm_matrix(int mode, int T, int k, int G, int S,
+                    const int32_t* topk_idx, const int32_t* pred_idx,
+                    const int32_t* row_of_assign, const int32_t* seg_offsets,
+                    int32_t* dispatch, int32_t* combine, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,8 @@ row's result travels rank of its segment -> owner(t).
 
 Plain loops over the assignments, in the order a = t*k + j.
 """
+import bisect
+
 import numpy as np
 
 from .plan import MODE_TOKEN
@@ -29,11 +31,11 @@ def owner_rank(t: int, T: int, G: int) -> int:
 
 
 def segment_of_row(row: int, seg_offsets) -> int:
-    """The segment sigma with seg_offsets[sigma] <= row < seg_offsets[sigma + 1]."""
-    for sigma in range(len(seg_offsets) - 1):
-        if seg_offsets[sigma] <= row < seg_offsets[sigma + 1]:
-            return sigma
-    raise ValueError("row outside every segment")
+    """The segment sigma with seg_offsets[sigma] <= row < seg_offsets[sigma + 1]
+    (seg_offsets is non-decreasing; empty segments have equal bounds)."""
+    if not seg_offsets[0] <= row < seg_offsets[-1]:
+        raise ValueError("row outside every segment")
+    return bisect.bisect_right(seg_offsets, row) - 1
 
 
 def comm_matrices(mode, topk_idx, pred_idx, row_of_assign, seg_offsets, G: int, S: int):
@@ -50,7 +52,7 @@ def comm_matrices(mode, topk_idx, pred_idx, row_of_assign, seg_offsets, G: int, 
         for j in range(k):
             dst = segment_of_row(int(rows[t, j]), so) // S
             src = own
-            if mode == MODE_TOKEN and int(idx[t, j]) in [int(v) for v in pred[t]]:
+            if mode == MODE_TOKEN and any(int(idx[t, j]) == int(v) for v in pred[t]):
                 src = dst
             dispatch[src, dst] += 1
             combine[dst, own] += 1

@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_packed_weights_bytes",
     "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
     "moe_grouped_ffn_time_next_call",
-    "moe_combine",
+    "moe_combine", "moe_comm_matrix",
 ]
 
 
@@ -82,6 +82,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn_time_next_call.argtypes = [ctypes.POINTER(vp)]
     lib.moe_combine.restype = c_int
     lib.moe_combine.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp]
+    lib.moe_comm_matrix.restype = c_int
+    lib.moe_comm_matrix.argtypes = [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, vp, vp]
     if path is None:
         _lib = lib
     return lib
@@ -280,6 +282,23 @@ def moe_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_w: torch
     _check(lib.moe_combine(_ptr(y_perm), dt, T, d, k, _ptr(row_of_assign), _ptr(topk_w), _ptr(out), _stream()),
            "moe_combine")
     return out
+
+
+def moe_comm_matrix(mode: int, topk_idx: torch.Tensor, pred_idx: Optional[torch.Tensor],
+                    row_of_assign: torch.Tensor, seg_offsets: torch.Tensor, G: int, S: int):
+    """Returns (dispatch, combine): int32 [G, G] counts of rows by [source rank, destination rank]."""
+    lib = load_library()
+    _need(topk_idx, torch.int32, "topk_idx")
+    _need(row_of_assign, torch.int32, "row_of_assign")
+    _need(seg_offsets, torch.int32, "seg_offsets")
+    if pred_idx is not None:
+        _need(pred_idx, torch.int32, "pred_idx")
+    T, k = topk_idx.shape
+    dispatch = torch.empty((G, G), dtype=torch.int32, device=topk_idx.device)
+    combine = torch.empty((G, G), dtype=torch.int32, device=topk_idx.device)
+    _check(lib.moe_comm_matrix(mode, T, k, G, S, _ptr(topk_idx), _ptr(pred_idx), _ptr(row_of_assign),
+                               _ptr(seg_offsets), _ptr(dispatch), _ptr(combine), _stream()), "moe_comm_matrix")
+    return dispatch, combine
 
 
 def moe_grouped_ffn_time_next_call(events) -> None:

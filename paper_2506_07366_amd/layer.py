@@ -125,6 +125,37 @@ class MoELayer:
         self.combine()
         return self.out
 
+    def comm_report(self, mode=None, pred_idx: Optional[torch.Tensor] = None, link_GBs: float = 153.6) -> dict:
+        """Rows (and bytes) that would cross the emulated ranks at dispatch and combine for the
+        last permutation (one C-ABI call + host read-back, off the timed path), next to the
+        closed forms of the paper's Background: (G-1)/G of all rows move when the placement is
+        balanced, and the busiest receiver gets (G-1)/G^2 * (max rank load / mean rank load).
+        ``time_us`` models a full mesh of point-to-point links (one per ordered pair of ranks,
+        ``link_GBs`` each way): the slowest pair decides."""
+        c = self.cfg
+        mode = c.mode if mode is None else mode
+        disp, comb = B.moe_comm_matrix(mode, self.topk_idx, pred_idx if mode == MODE_TOKEN else None,
+                                       self.perm["row_of_assign"], self.perm["seg_offsets"], c.G, c.S)
+        disp = disp.cpu().numpy().astype(np.int64)
+        comb = comb.cpu().numpy().astype(np.int64)
+        row_bytes = c.d * (2 if c.dtype == "bf16" else 4)
+        A = int(disp.sum())
+        load = disp.sum(axis=0)
+
+        def side(m):
+            off = m - np.diag(np.diag(m))
+            return dict(crossing_rows=int(off.sum()), crossing_frac=float(off.sum() / A) if A else 0.0,
+                        max_inbound_rows=int(off.sum(axis=0).max()), max_outbound_rows=int(off.sum(axis=1).max()),
+                        max_pair_rows=int(off.max()), bytes=int(off.sum()) * row_bytes,
+                        time_us=float(off.max() * row_bytes / (link_GBs * 1e9) * 1e6))
+
+        rank_skew = float(load.max() * c.G / A) if A else 0.0
+        return dict(mode=mode, dispatch=side(disp), combine=side(comb),
+                    balanced_crossing_frac=(c.G - 1) / c.G,
+                    bottleneck_inbound_frac_model=(c.G - 1) * rank_skew / c.G**2,
+                    bottleneck_inbound_frac=float((disp.sum(axis=0) - np.diag(disp)).max() / A) if A else 0.0,
+                    dispatch_matrix=disp.tolist() if c.G <= 8 else None)
+
     def load_report(self) -> dict:
         """Host read-back (off the timed path): per-rank rows, makespan, imbalance and
         skewness (most popular expert's tokens / average tokens per expert)."""

@@ -49,6 +49,9 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.moe_plan_duplicates(7, None, 8, 4, 3, 2, None, None, None, None, None) == -1   # bad mode
     assert lib.moe_combine(None, 1, 4, 100, 2, None, None, None, None) == -2  # row bytes not a multiple of 16
     assert lib.moe_combine(None, 5, 4, 128, 2, None, None, None, None) == -1  # bad dtype
+    assert lib.moe_comm_matrix(9, 4, 2, 2, 2, None, None, None, None, None, None, None) == -1   # bad mode
+    assert lib.moe_comm_matrix(0, 4, 2, 300, 2, None, None, None, None, None, None, None) == -2  # G above the limit
+    assert lib.moe_comm_matrix(0, 4, 2, 2, 2, None, None, None, None, None, None, None) == -1   # no output tables
     assert lib.moe_permute_workspace_bytes(4096, 8, 2, 8, 2) > 0
     assert lib.moe_grouped_ffn_workspace_bytes(8192, 4096, 14336, 16, 1) >= 8192 * 14336 * 2
 

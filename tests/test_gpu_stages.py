@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from oracle import route_topk, histogram, plan_duplicates, permute, combine
+from oracle.comm import comm_matrices
 from paper_2506_07366_amd import binding as B
 from paper_2506_07366_amd import workloads as wl
 from gpu_util import Case, dev_i32, to_host_f32
@@ -71,6 +72,15 @@ def test_integer_stages_on_config(name):
     assert np.array_equal(out["assign_of_row"].cpu().numpy(), case.perm["assign_of_row"])
     assert np.array_equal(out["rank_load"].cpu().numpy(), case.perm["rank_load"])
     assert int(out["rank_load"].sum()) == cfg.A
+
+    # rows crossing the emulated ranks, from the permutation just computed
+    disp, comb = B.moe_comm_matrix(cfg.mode, idx, pred_idx if cfg.mode == wl.MODE_TOKEN else None,
+                                   out["row_of_assign"], out["seg_offsets"], cfg.G, cfg.S)
+    rdisp, rcomb = comm_matrices(cfg.mode, case.idx, case.pred_idx, case.perm["row_of_assign"],
+                                 case.perm["seg_offsets"], cfg.G, cfg.S)
+    assert np.array_equal(disp.cpu().numpy(), rdisp)
+    assert np.array_equal(comb.cpu().numpy(), rcomb)
+    assert np.array_equal(disp.cpu().numpy().sum(axis=0), case.perm["rank_load"])
 
 
 # ---------------------------------------------------------------- histogram
@@ -181,3 +191,28 @@ def test_combine(dtype, T, k, d):
         out1 = B.moe_combine(to_device(wl.to_storage(y, dtype), dtype), dev_i32(rows),
                              torch.ones((T, 1), device="cuda"), T, 1)
         assert np.array_equal(to_host_f32(out1), y[rows])
+
+
+# ---------------------------------------------------------------- cross-rank traffic
+@pytest.mark.parametrize("mode,T,E,k,G,S", [(0, 1, 1, 1, 1, 1), (1, 333, 12, 3, 4, 5), (2, 333, 12, 3, 4, 5),
+                                            (2, 5000, 64, 6, 8, 10), (1, 2000, 256, 4, 128, 4),
+                                            (2, 1500, 256, 8, 256, 2), (0, 777, 10, 2, 5, 2)])
+def test_comm_matrix_small(mode, T, E, k, G, S):
+    cfg = wl.MoEConfig("comm", T=T, d=16, ffn=8, E=E, k=k, G=G, S=S, dtype="f32", mode=mode, alpha=0.3,
+                       sigma_pred=0.3, acc=0.7, seed=11)
+    case = Case(cfg, with_x=False)
+    idx = dev_i32(case.idx)
+    pred_idx = case.dev_pred_idx()
+    disp, comb = B.moe_comm_matrix(mode, idx, pred_idx if mode == wl.MODE_TOKEN else None,
+                                   dev_i32(case.perm["row_of_assign"]), dev_i32(case.perm["seg_offsets"]), G, S)
+    rdisp, rcomb = comm_matrices(mode, case.idx, case.pred_idx, case.perm["row_of_assign"],
+                                 case.perm["seg_offsets"], G, S)
+    assert np.array_equal(disp.cpu().numpy(), rdisp)
+    assert np.array_equal(comb.cpu().numpy(), rcomb)
+
+
+def test_comm_matrix_empty_batch():
+    z = torch.zeros((0, 2), dtype=torch.int32, device="cuda")
+    so = torch.zeros(4 * 2 + 1, dtype=torch.int32, device="cuda")
+    disp, comb = B.moe_comm_matrix(0, z, None, torch.zeros(0, dtype=torch.int32, device="cuda"), so, 4, 2)
+    assert int(disp.abs().sum()) == 0 and int(comb.abs().sum()) == 0

@@ -4,7 +4,7 @@ import pytest
 
 from conftest import read_golden
 from oracle import route_topk, histogram, plan_duplicates, permute, home_slot, skewness
-from oracle.comm import comm_matrices, crossing_rows, max_inbound, owner_rank
+from oracle.comm import comm_matrices, crossing_rows, max_inbound, owner_rank, segment_of_row
 from paper_2506_07366_amd import workloads as wl
 
 SMALL = wl.MoEConfig("small", T=300, d=16, ffn=8, E=12, k=3, G=4, S=5, dtype="f32", mode=1,
@@ -130,3 +130,14 @@ def test_duplication_lowers_the_bottleneck_inbound():
     _, _, _, disp1, _ = run_case(cfg)
     _, _, _, disp0, _ = run_case(cfg.replace(mode=0))
     assert disp1.sum(axis=0).max() <= disp0.sum(axis=0).max()
+
+
+def test_segment_lookup_against_a_linear_scan():
+    so = [0, 0, 3, 3, 3, 7, 8, 8]
+    for row in range(8):
+        want = [s for s in range(len(so) - 1) if so[s] <= row < so[s + 1]]
+        assert len(want) == 1 and segment_of_row(row, so) == want[0]
+    with pytest.raises(ValueError):
+        segment_of_row(8, so)
+    with pytest.raises(ValueError):
+        segment_of_row(-1, so)
