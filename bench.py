@@ -279,6 +279,55 @@ def main():
                                                         cfg.G, cfg.S))
     comm["kernel_ms"] = stage_ms.pop("comm_matrix")
 
+    # Distribution-Only predictor over a stream of batches with one fixed expert popularity:
+    # the running estimate n_i/N predicts each batch before it is seen; the plan is rebuilt
+    # every F batches and reused in between (placement frequency)
+    def predictor_stream(n_batches=16, every=(1, 4, 16)):
+        E, G, S = cfg.E, cfg.G, cfg.S
+        batches = []
+        for bi in range(n_batches):
+            lg = torch.from_numpy(wl.gen_logits_batch(cfg, bi)).cuda()
+            idx_b, _ = B.moe_route_topk(lg, cfg.k)
+            batches.append((idx_b, B.moe_histogram(idx_b, E)))
+        out = {"batches": n_batches, "imbalance_mean": {}}
+
+        def imbalance(mode, idx_b, hist_b, hp, se, sq):
+            perm = B.moe_permute(mode, None, idx_b, None, hist_b, hp, se, sq, E, G, S)
+            return float(perm["rank_load"].max().item()) * G / cfg.A
+
+        se0, sq0, _, _ = B.moe_plan_duplicates(0, batches[0][1], G, S, cfg.cmax)
+        out["imbalance_mean"]["no_duplication"] = float(np.mean(
+            [imbalance(0, i_, h_, h_, se0, sq0) for i_, h_ in batches[1:]]))
+        errs, skews = [], []
+        for F in every:
+            counts = torch.zeros(E, dtype=torch.int64, device="cuda")
+            vals = []
+            for bi, (idx_b, hist_b) in enumerate(batches):
+                if bi > 0:      # batch 0 only trains the estimate
+                    if (bi - 1) % F == 0:
+                        hp = B.moe_predictor_predict(counts, cfg.A)
+                        se, sq, _, _ = B.moe_plan_duplicates(1, hp, G, S, cfg.cmax)
+                    vals.append(imbalance(1, idx_b, hist_b, hp, se, sq))
+                    if F == 1:
+                        ht = hist_b.cpu().numpy().astype(np.float64)
+                        hpn = hp.cpu().numpy().astype(np.float64)
+                        errs.append(float(np.mean(np.abs(hpn / hpn.sum() - ht / ht.sum())) * E))
+                        skews.append(float(ht.max() * E / ht.sum()))
+                B.moe_predictor_update(hist_b, counts)
+            out["imbalance_mean"][f"replan_every_{F}"] = float(np.mean(vals))
+        out["error_rate_mean"] = float(np.mean(errs))
+        out["skewness_mean"] = float(np.mean(skews))
+        counts = torch.zeros(E, dtype=torch.int64, device="cuda")
+        B.moe_predictor_update(batches[0][1], counts)
+        hp = torch.empty(E, dtype=torch.int32, device="cuda")
+        time_stage("predict", lambda: B.moe_predictor_predict(counts, cfg.A, out=hp), reps=20)
+        time_stage("update", lambda: B.moe_predictor_update(batches[0][1], counts), reps=20)
+        out["predict_ms"] = stage_ms.pop("predict")
+        out["update_ms"] = stage_ms.pop("update")
+        return out
+
+    stream = predictor_stream()
+
     # the other row-gather variant, timed the same way (extra, not the headline)
     other = MoELayer(cfg, fused_gather=not args.fused_gather)
     other.packed = layer.packed
@@ -300,7 +349,7 @@ def main():
         "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
-        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
+        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm, "predictor_stream": stream,
         other_key: {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"},
     }
     if not args.no_cpu_baseline:

@@ -232,6 +232,22 @@ int moe_comm_matrix(int mode, int T, int k, int G, int S,
                     const int32_t* row_of_assign, const int32_t* seg_offsets,
                     int32_t* dispatch, int32_t* combine, void* stream);
 
+/*
+ * Distribution-Only predictor (Section 3.2.1, Eq. (1); Appendix A): the maximum-likelihood
+ * estimate of a layer's expert distribution is p_hat_i = n_i / N over all tokens seen so
+ * far (a running average when the data come in batches).
+ *   moe_predictor_update : counts[e] += hist[e]          (hist: one batch's moe_histogram)
+ *   moe_predictor_predict: hist_pred = p_hat * A_next brought to integers that sum to
+ *                          A_next by largest remainder (ties -> lowest expert); uniform
+ *                          while nothing has been seen (all counts zero).
+ *   hist [E] int32 device in; counts [E] int64 device in/out, owned and zeroed by the caller
+ *   before the first batch, total below 2^62; hist_pred [E] int32 device out, a valid
+ *   `hist_pred` for moe_plan_duplicates / moe_permute in MOE_MODE_DISTRIBUTION.
+ * E <= MOE_MAX_EXPERTS, 0 <= A_next < 2^31.  Exact integer arithmetic.
+ */
+int moe_predictor_update(const int32_t* hist, int E, int64_t* counts, void* stream);
+int moe_predictor_predict(const int64_t* counts, int E, int64_t A_next, int32_t* hist_pred, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_packed_weights_bytes",
     "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
     "moe_grouped_ffn_time_next_call",
-    "moe_combine", "moe_comm_matrix",
+    "moe_combine", "moe_comm_matrix", "moe_predictor_update", "moe_predictor_predict",
 ]
 
 
@@ -82,6 +82,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn_time_next_call.argtypes = [ctypes.POINTER(vp)]
     lib.moe_combine.restype = c_int
     lib.moe_combine.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp]
+    lib.moe_predictor_update.restype = c_int
+    lib.moe_predictor_update.argtypes = [vp, c_int, vp, vp]
+    lib.moe_predictor_predict.restype = c_int
+    lib.moe_predictor_predict.argtypes = [vp, c_int, c_i64, vp, vp]
     lib.moe_comm_matrix.restype = c_int
     lib.moe_comm_matrix.argtypes = [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, vp, vp]
     if path is None:
@@ -299,6 +303,27 @@ def moe_comm_matrix(mode: int, topk_idx: torch.Tensor, pred_idx: Optional[torch.
     _check(lib.moe_comm_matrix(mode, T, k, G, S, _ptr(topk_idx), _ptr(pred_idx), _ptr(row_of_assign),
                                _ptr(seg_offsets), _ptr(dispatch), _ptr(combine), _stream()), "moe_comm_matrix")
     return dispatch, combine
+
+
+def moe_predictor_update(hist: torch.Tensor, counts: torch.Tensor) -> None:
+    """counts[e] += hist[e] (counts: int64 [E], zeroed by the caller before the first batch)."""
+    lib = load_library()
+    _need(hist, torch.int32, "hist")
+    _need(counts, torch.int64, "counts")
+    if hist.numel() != counts.numel():
+        raise MoeGpsError("hist and counts must have one entry per expert")
+    _check(lib.moe_predictor_update(_ptr(hist), hist.numel(), _ptr(counts), _stream()), "moe_predictor_update")
+
+
+def moe_predictor_predict(counts: torch.Tensor, A_next: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Predicted histogram (int32 [E], sums to A_next) from the cumulative counts."""
+    lib = load_library()
+    _need(counts, torch.int64, "counts")
+    if out is None:
+        out = torch.empty(counts.numel(), dtype=torch.int32, device=counts.device)
+    _check(lib.moe_predictor_predict(_ptr(counts), counts.numel(), A_next, _ptr(out), _stream()),
+           "moe_predictor_predict")
+    return out
 
 
 def moe_grouped_ffn_time_next_call(events) -> None:

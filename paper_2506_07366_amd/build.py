@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmoegps.so")
 SOURCES = ["api.hip", "route_topk.hip", "histogram.hip", "plan.hip", "permute.hip", "grouped_ffn.hip",
-           "combine.hip", "comm.hip"]
+           "combine.hip", "comm.hip", "predictor.hip"]
 # packed-fp32 code generation is switched off for every HIP translation unit
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
              "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -149,6 +149,15 @@ def gen_logits(cfg: MoEConfig) -> np.ndarray:
     return (z + b[None, :]).astype(np.float32)
 
 
+def gen_logits_batch(cfg: MoEConfig, batch: int) -> np.ndarray:
+    """Batch ``batch`` of a stream of router logits with one fixed expert popularity
+    (the i.i.d. setting of the Distribution-Only predictor): the bias of gen_logits,
+    fresh N(0, 1) noise per batch.  Batch 0 is not gen_logits' batch."""
+    b = np.log(expert_popularity(cfg)).astype(np.float32)
+    z = _rng(cfg, 7, batch).standard_normal((cfg.T, cfg.E), dtype=np.float32)
+    return (z + b[None, :]).astype(np.float32)
+
+
 # ---------------------------------------------------------------------------
 # activations and weights
 # ---------------------------------------------------------------------------

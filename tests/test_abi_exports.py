@@ -52,6 +52,9 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.moe_comm_matrix(9, 4, 2, 2, 2, None, None, None, None, None, None, None) == -1   # bad mode
     assert lib.moe_comm_matrix(0, 4, 2, 300, 2, None, None, None, None, None, None, None) == -2  # G above the limit
     assert lib.moe_comm_matrix(0, 4, 2, 2, 2, None, None, None, None, None, None, None) == -1   # no output tables
+    assert lib.moe_predictor_update(None, 8, None, None) == -1                  # no buffers
+    assert lib.moe_predictor_predict(None, 2000, 10, None, None) == -2          # E above the limit
+    assert lib.moe_predictor_predict(None, 8, -1, None, None) == -1             # negative batch size
     assert lib.moe_permute_workspace_bytes(4096, 8, 2, 8, 2) > 0
     assert lib.moe_grouped_ffn_workspace_bytes(8192, 4096, 14336, 16, 1) >= 8192 * 14336 * 2
 
