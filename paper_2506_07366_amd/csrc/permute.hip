@@ -138,24 +138,47 @@ __device__ __forceinline__ long long wave_incl_scan(long long v) {
     return v;
 }
 
-// In-place exclusive scan down one column of a [nb, ncols] table by one wavefront
-// (lanes take consecutive rows); returns the column total.
-__device__ __forceinline__ int wave_column_scan(int32_t* table, int nb, int ncols, int col) {
+// inclusive prefix sum of 32-bit counts over the 64 lanes of a wavefront
+__device__ __forceinline__ int wave_incl_scan_i32(int v) {
     const int lane = threadIdx.x & (kWave - 1);
-    int carry = 0;
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        const int o = __shfl_up(v, m, kWave);
+        if (lane >= m) v += o;
+    }
+    return v;
+}
+
+// In-place exclusive scan down NC neighbouring columns (col0 .. col0 + NC - 1, those
+// below ncols) of a [nb, ncols] table by one wavefront: lanes take consecutive rows, the
+// NC loads of a step are independent and go out together.  total[i] = column sums.
+template <int NC>
+__device__ __forceinline__ void wave_columns_scan(int32_t* table, int nb, int ncols, int col0, int total[NC]) {
+    const int lane = threadIdx.x & (kWave - 1);
+    int carry[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) carry[i] = 0;
     for (int b0 = 0; b0 < nb; b0 += kWave) {
         const int b = b0 + lane;
-        const int c = b < nb ? table[(size_t)b * ncols + col] : 0;
-        const int incl = (int)wave_incl_scan(c);
-        if (b < nb) table[(size_t)b * ncols + col] = carry + incl - c;
-        carry += __shfl(incl, kWave - 1, kWave);
+        int c[NC], incl[NC];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) c[i] = (b < nb && col0 + i < ncols) ? table[(size_t)b * ncols + col0 + i] : 0;
+#pragma unroll
+        for (int i = 0; i < NC; ++i) incl[i] = wave_incl_scan_i32(c[i]);
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            if (b < nb && col0 + i < ncols) table[(size_t)b * ncols + col0 + i] = carry[i] + incl[i] - c[i];
+            carry[i] += __shfl(incl[i], kWave - 1, kWave);
+        }
     }
-    return carry;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) total[i] = carry[i];
 }
 
 // chunk bases per expert (in place) and the replica tables of the plan; one
-// wavefront per expert column
-__global__ __launch_bounds__(1024) void perm_scan1_kernel(int mode, int nb, int E, int G, int S,
+// wavefront per expert column, columns dealt over the whole grid
+constexpr int kScan1Threads = 256;
+__global__ __launch_bounds__(kScan1Threads) void perm_scan1_kernel(int mode, int nb, int E, int G, int S,
                                                            const int32_t* __restrict__ hist_true,
                                                            const int32_t* __restrict__ hist_pred,
                                                            const int32_t* __restrict__ slot_expert,
@@ -164,8 +187,9 @@ __global__ __launch_bounds__(1024) void perm_scan1_kernel(int mode, int nb, int 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
     const unsigned long long lt = (1ull << lane) - 1ull;
-    for (int e = wave; e < E; e += nwaves) {
-        wave_column_scan(ws.bh1, nb, E, e);
+    for (int e = blockIdx.x * nwaves + wave; e < E; e += gridDim.x * nwaves) {
+        int unused[1];
+        wave_columns_scan<1>(ws.bh1, nb, E, e, unused);
         // replicas of e in ascending slot id with the upper bound of their range
         long long n_true = 0, n_hat = 0;
         if (mode == MOE_MODE_DISTRIBUTION) {
@@ -277,9 +301,15 @@ __global__ __launch_bounds__(1024) void perm_scan2_kernel(int nb, int G, int S, 
     const int nseg = G * S;
     const int tid = threadIdx.x;
     const int wave = tid / kWave, nwaves = blockDim.x / kWave;
-    for (int s = wave; s < nseg; s += nwaves) {  // one wavefront per segment column
-        const int total = wave_column_scan(ws.bh2, nb, nseg, s);
-        if ((tid & (kWave - 1)) == 0) tot[s] = total;
+    constexpr int NC = 4;  // neighbouring segment columns one wavefront scans together
+    for (int s0 = wave * NC; s0 < nseg; s0 += nwaves * NC) {
+        int total[NC];
+        wave_columns_scan<NC>(ws.bh2, nb, nseg, s0, total);
+        if ((tid & (kWave - 1)) == 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i)
+                if (s0 + i < nseg) tot[s0 + i] = total[i];
+        }
     }
     __syncthreads();
     block_exclusive_scan_2048(tot, nseg, wave_sum);
@@ -393,8 +423,8 @@ extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int
         if ((rc = check_launch()) != MOE_OK) return rc;
     }
     if (mode != MOE_MODE_NONE) {
-        hipLaunchKernelGGL(perm_scan1_kernel, dim3(1), dim3(1024), 0, st, mode, nb, E, G, S, hist_true, hist_pred,
-                           slot_expert, slot_quota, ws);
+        hipLaunchKernelGGL(perm_scan1_kernel, dim3(ceil_div(E, kScan1Threads / kWave)), dim3(kScan1Threads), 0, st,
+                           mode, nb, E, G, S, hist_true, hist_pred, slot_expert, slot_quota, ws);
         if ((rc = check_launch()) != MOE_OK) return rc;
     }
     if (nb > 0) {
