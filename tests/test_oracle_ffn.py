@@ -130,3 +130,45 @@ def test_expert_bytes_arithmetic():
     g = read_golden("expert_bytes.txt")
     assert 4096 * 14336 * 2 * 2 == g["bytes"][0]
     assert g["bytes"][0] / g["link_bytes_per_s"][0] * 1e3 == pytest.approx(g["ms"][0], rel=0.2)
+
+
+# ---------------------------------------------------------------- ReLU form (Switch-Transformer FFN)
+def test_relu_ffn_equals_naive_loops_and_torch():
+    from oracle.ffn import ffn_rows_relu, ffn_rows_relu_naive
+    rng = np.random.default_rng(20)
+    x = rng.standard_normal((4, 6))
+    W1 = rng.standard_normal((6, 5))
+    W2 = rng.standard_normal((5, 6))
+    y = ffn_rows_relu(x, W1, W2)
+    yn = np.array(ffn_rows_relu_naive(x.tolist(), W1.tolist(), W2.tolist()))
+    assert np.allclose(y, yn, rtol=1e-13, atol=1e-13)
+    ref = torch.relu(torch.from_numpy(x) @ torch.from_numpy(W1)) @ torch.from_numpy(W2)
+    assert np.allclose(y, ref.numpy(), rtol=1e-13, atol=1e-13)
+
+
+def test_relu_ffn_closed_forms():
+    from oracle.ffn import ffn_rows_relu
+    # scalar: x=2, W1=3 -> h=6, W2=0.5 -> 3; negative pre-activation -> 0
+    assert ffn_rows_relu([[2.0]], [[3.0]], [[0.5]])[0, 0] == 3.0
+    assert ffn_rows_relu([[2.0]], [[-3.0]], [[0.5]])[0, 0] == 0.0
+    rng = np.random.default_rng(21)
+    x = np.abs(rng.standard_normal((5, 7)))
+    W1 = np.abs(rng.standard_normal((7, 4)))
+    W2 = rng.standard_normal((4, 7))
+    # all pre-activations positive: the block is the plain product of the three matrices
+    assert np.allclose(ffn_rows_relu(x, W1, W2), x @ W1 @ W2, rtol=1e-13)
+    # all negative: zero
+    assert np.all(ffn_rows_relu(x, -W1, W2) == 0.0)
+    # positively homogeneous: f(a x) = a f(x) for a > 0 (not true of the SwiGLU form)
+    assert np.allclose(ffn_rows_relu(3.0 * x, W1 - 0.5, W2), 3.0 * ffn_rows_relu(x, W1 - 0.5, W2), rtol=1e-12)
+
+
+def test_grouped_relu_uses_the_segments_expert():
+    from oracle.ffn import ffn_rows_relu
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal((6, 4))
+    W1 = rng.standard_normal((3, 4, 5))
+    W2 = rng.standard_normal((3, 5, 4))
+    y = grouped_ffn(x, [0, 2, 2, 6], [2, -1, 0], W1, None, W2)
+    assert np.array_equal(y[0:2], ffn_rows_relu(x[0:2], W1[2], W2[2]))
+    assert np.array_equal(y[2:6], ffn_rows_relu(x[2:6], W1[0], W2[0]))
