@@ -51,7 +51,7 @@ def measured_traffic(config_name):
 
 def describe(cfg):
     mode = {0: "no prediction", 1: "distribution-only", 2: "token-to-expert"}[cfg.mode]
-    return (f"{cfg.name}: T={cfg.T} d={cfg.d} ffn={cfg.ffn} E={cfg.E} top-{cfg.k} {cfg.dtype} "
+    return (f"{cfg.name}: T={cfg.T} d={cfg.d} ffn={cfg.ffn} E={cfg.E} top-{cfg.k} {cfg.dtype} {cfg.act} FFN "
             f"G={cfg.G}x{cfg.S} slots, {mode} plan")
 
 
@@ -80,8 +80,12 @@ def cpu_baseline(cfg, case_inputs, max_rows=4096):
     t0 = time.perf_counter()
     for s in chosen:
         e = int(plan.slot_expert[s])
-        y = oracle.ffn_rows(perm["x_perm"][so[s]:so[s + 1]], wl.from_storage(Ws[0][e], cfg.dtype),
-                            wl.from_storage(Ws[1][e], cfg.dtype), wl.from_storage(Ws[2][e], cfg.dtype))
+        if cfg.act == "relu":
+            y = oracle.ffn.ffn_rows_relu(perm["x_perm"][so[s]:so[s + 1]], wl.from_storage(Ws[0][e], cfg.dtype),
+                                         wl.from_storage(Ws[2][e], cfg.dtype))
+        else:
+            y = oracle.ffn_rows(perm["x_perm"][so[s]:so[s + 1]], wl.from_storage(Ws[0][e], cfg.dtype),
+                                wl.from_storage(Ws[1][e], cfg.dtype), wl.from_storage(Ws[2][e], cfg.dtype))
     t_ffn = time.perf_counter() - t0
     # combine on the same number of rows
     nt = max(1, rows // cfg.k)
@@ -189,13 +193,14 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
 
-    flops1 = 4.0 * cfg.A * cfg.d * cfg.ffn      # gate + up products
+    flops1 = (2.0 if cfg.act == "relu" else 4.0) * cfg.A * cfg.d * cfg.ffn   # gate + up products (ReLU form: one)
     flops2 = 2.0 * cfg.A * cfg.d * cfg.ffn      # down product
     if bf16:
         g1_ms = float(np.mean([q[0].elapsed_time(q[1]) for q in evs]))
         g2_ms = float(np.mean([q[2].elapsed_time(q[3]) for q in evs]))
         achieved = flops1 / (g1_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<swiglu> (gate/up product)",
+        roofline = {"bound": "mfma", "kernel": ("grouped_gemm_bf16_kernel<relu> (first product)" if cfg.act == "relu"
+                                                else "grouped_gemm_bf16_kernel<swiglu> (gate/up product)"),
                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config), "avg_ms": g1_ms,
                     "down_product": {"avg_ms": g2_ms, "achieved": flops2 / (g2_ms * 1e-3) / 1e12,
@@ -328,18 +333,22 @@ def main():
 
     stream = predictor_stream()
 
-    # the other row-gather variant, timed the same way (extra, not the headline)
-    other = MoELayer(cfg, fused_gather=not args.fused_gather)
-    other.packed = layer.packed
-    for _ in range(max(1, args.warmup)):
-        other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
-    torch.cuda.synchronize()
-    other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the other row-gather variant, timed the same way (extra, not the headline; the fused
+    # gather exists for the SwiGLU form only)
     other_key = "six_call_path" if args.fused_gather else "fused_gather_path"
+    other_result = None
+    if cfg.act != "relu":
+        other = MoELayer(cfg, fused_gather=not args.fused_gather)
+        other.packed = layer.packed
+        for _ in range(max(1, args.warmup)):
+            other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+        torch.cuda.synchronize()
+        other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        other_result = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
 
     result = {
         "metric": "MoE-layer tokens/s (route+plan+permute+FFN+combine); FFN MFMA % of peak",
@@ -350,7 +359,7 @@ def main():
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
         "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm, "predictor_stream": stream,
-        other_key: {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"},
+        other_key: other_result,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, (logits_h, x_h, Ws, hist_pred_h, pred_idx_h, wl))

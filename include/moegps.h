@@ -191,6 +191,24 @@ int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t
                            void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The ReLU form of the expert FFN (Discussion, "Generality across model architectures":
+ * Switch Transformer uses ReLU in its FFN, with top-1 routing):
+ *     y_perm[r] = max(x_perm[r] W1_e, 0) W2_e        no gate matrix, no biases
+ * moe_pack_weights_relu repacks W1 [E, d, ffn] and W2 [E, ffn, d] into
+ * moe_packed_weights_relu_bytes(E, d, ffn, dtype) bytes; moe_grouped_ffn_relu takes the
+ * arguments of moe_grouped_ffn (same workspace size, same limits, same precision rules:
+ * bf16 storage, fp32 accumulation, the hidden activation rounded to bf16) with that
+ * packed buffer.
+ */
+size_t moe_packed_weights_relu_bytes(int E, int d, int ffn, int dtype);
+int moe_pack_weights_relu(const void* W1, const void* W2, int dtype,
+                          int E, int d, int ffn, void* packed, void* stream);
+int moe_grouped_ffn_relu(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
+                         const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
+                         int seg_begin, int seg_end, const void* packed,
+                         void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Optional timing hook for the next moe_grouped_ffn / moe_grouped_ffn_gather call on this host thread:
  * events[0..3] are hipEvent_t handles (as void*) that the call records on its
  * stream before and after its first product (gate/up + SwiGLU) and before and

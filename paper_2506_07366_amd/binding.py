@@ -27,6 +27,7 @@ EXPORTS = [
     "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
     "moe_grouped_ffn_time_next_call",
     "moe_combine", "moe_comm_matrix", "moe_predictor_update", "moe_predictor_predict",
+    "moe_packed_weights_relu_bytes", "moe_pack_weights_relu", "moe_grouped_ffn_relu",
 ]
 
 
@@ -75,6 +76,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn.restype = c_int
     lib.moe_grouped_ffn.argtypes = [vp, c_int, c_i64, c_int, c_int, c_int, vp, vp, c_int, c_int, c_int,
                                     vp, vp, vp, c_sz, vp]
+    lib.moe_packed_weights_relu_bytes.restype = c_sz
+    lib.moe_packed_weights_relu_bytes.argtypes = [c_int] * 4
+    lib.moe_pack_weights_relu.restype = c_int
+    lib.moe_pack_weights_relu.argtypes = [vp, vp, c_int, c_int, c_int, c_int, vp, vp]
+    lib.moe_grouped_ffn_relu.restype = c_int
+    lib.moe_grouped_ffn_relu.argtypes = lib.moe_grouped_ffn.argtypes
     lib.moe_grouped_ffn_gather.restype = c_int
     lib.moe_grouped_ffn_gather.argtypes = [vp, c_int, c_int, c_int, vp, c_int, c_int, c_int, vp, vp, c_int, c_int,
                                            c_int, vp, vp, vp, c_sz, vp]
@@ -224,9 +231,25 @@ def moe_grouped_ffn_workspace_bytes(A: int, d: int, ffn: int, nseg: int, dtype: 
     return int(load_library().moe_grouped_ffn_workspace_bytes(A, d, ffn, nseg, dtype))
 
 
+def moe_pack_weights_relu(W1: torch.Tensor, W2: torch.Tensor) -> torch.Tensor:
+    """Packed weights of the ReLU form of the FFN (W1 [E, d, ffn], W2 [E, ffn, d])."""
+    lib = load_library()
+    dt = dtype_code(W1)
+    _need(W2, W1.dtype, "W2")
+    E, d, ffn = W1.shape
+    if tuple(W2.shape) != (E, ffn, d):
+        raise MoeGpsError("weight shapes must be W1 [E,d,ffn] and W2 [E,ffn,d]")
+    packed = torch.empty(int(lib.moe_packed_weights_relu_bytes(E, d, ffn, dt)), dtype=torch.uint8, device=W1.device)
+    _check(lib.moe_pack_weights_relu(_ptr(W1), _ptr(W2), dt, E, d, ffn, _ptr(packed), _stream()),
+           "moe_pack_weights_relu")
+    return packed
+
+
 def moe_grouped_ffn(x_perm: torch.Tensor, seg_offsets: torch.Tensor, slot_expert: torch.Tensor, packed: torch.Tensor,
                     E: int, ffn: int, seg_begin: int = 0, seg_end: Optional[int] = None,
-                    workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                    workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                    relu: bool = False) -> torch.Tensor:
+    """``relu=True`` calls moe_grouped_ffn_relu (``packed`` from moe_pack_weights_relu)."""
     lib = load_library()
     dt = dtype_code(x_perm)
     if not x_perm.is_contiguous() or not x_perm.is_cuda:
@@ -241,9 +264,10 @@ def moe_grouped_ffn(x_perm: torch.Tensor, seg_offsets: torch.Tensor, slot_expert
     need = moe_grouped_ffn_workspace_bytes(A, d, ffn, nseg, dt)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x_perm.device)
-    _check(lib.moe_grouped_ffn(_ptr(x_perm), dt, A, d, ffn, E, _ptr(seg_offsets), _ptr(slot_expert), nseg,
-                               seg_begin, seg_end, _ptr(packed), _ptr(y), _ptr(workspace), workspace.numel(),
-                               _stream()), "moe_grouped_ffn")
+    fn = lib.moe_grouped_ffn_relu if relu else lib.moe_grouped_ffn
+    _check(fn(_ptr(x_perm), dt, A, d, ffn, E, _ptr(seg_offsets), _ptr(slot_expert), nseg, seg_begin, seg_end,
+              _ptr(packed), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
+           "moe_grouped_ffn_relu" if relu else "moe_grouped_ffn")
     return y
 
 

@@ -185,7 +185,12 @@ __device__ __forceinline__ int swz(int row) {
     return 0;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
+// EPI selects what happens to the accumulators before they are stored: kEpiNone (plain
+// product), kEpiSwiglu (silu(gate) * up on interleaved column pairs, half as many output
+// columns), kEpiRelu (max(., 0)).
+constexpr int kEpiNone = 0, kEpiSwiglu = 1, kEpiRelu = 2;
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
     const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
@@ -193,6 +198,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int32_t* __restrict__ queues,
     int N, int K, int group_n,
     const int32_t* __restrict__ gather_rows, int gather_div) {  // optional: A row r is A[gather_rows[r] / gather_div]
+    constexpr bool SWIGLU = EPI == kEpiSwiglu;
     constexpr int NW = WGM * WGN;
     constexpr int NT = NW * 64;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -470,6 +476,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                             for (int c = 0; c < 4; ++c) {
                                 if (SWIGLU)
                                     v[c] = silu_f(acc[i][2 * jo][g * 4 + c]) * acc[i][2 * jo + 1][g * 4 + c];
+                                else if (EPI == kEpiRelu)
+                                    v[c] = fmaxf(acc[i][jo][g * 4 + c], 0.f);
                                 else
                                     v[c] = acc[i][jo][g * 4 + c];
                             }
@@ -496,7 +504,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
                                                                 const MTile* __restrict__ mtiles,
                                                                 const int32_t* __restrict__ n_mtiles_ptr, int N,
                                                                 int K, const int32_t* __restrict__ gather_rows,
-                                                                int gather_div) {
+                                                                int gather_div, int relu) {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float sA[BK][BM + 4];
     __shared__ float sB1[BK][BN + 4];
@@ -553,6 +561,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
                 if (row < mt.rows && col < N) {
                     float v = acc1[i][j];
                     if (SWIGLU) v = v / (1.0f + expf(-v)) * acc3[i][j];
+                    else if (relu) v = fmaxf(v, 0.f);
                     C[(size_t)(mt.row0 + row) * ldc + col] = v;
                 }
             }
@@ -600,37 +609,39 @@ struct GemmVariant {
                  int, int, const int32_t*, int);
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, bool SWIGLU>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI>
 static GemmVariant make_variant() {
     GemmVariant v;
     v.bm = BM;
     v.bn = BN;
     v.lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
     v.threads = WGM * WGN * 64;
-    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, SWIGLU>;
+    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI>;
     return v;
 }
 
 // tile shapes built into the library; index 0 is the default
 static const GemmVariant kGemm1[] = {
-    make_variant<128, 256, 64, 2, 2, 3, true>(),
-    make_variant<256, 256, 64, 2, 2, 2, true>(),
-    make_variant<128, 512, 32, 1, 4, 3, true>(),
-    make_variant<256, 256, 64, 2, 4, 2, true>(),
-    make_variant<64, 256, 64, 1, 4, 3, true>(),
-    make_variant<256, 256, 32, 2, 4, 4, true>(),
-    make_variant<128, 256, 64, 2, 4, 3, true>(),
+    make_variant<128, 256, 64, 2, 2, 3, kEpiSwiglu>(),
+    make_variant<256, 256, 64, 2, 2, 2, kEpiSwiglu>(),
+    make_variant<128, 512, 32, 1, 4, 3, kEpiSwiglu>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu>(),
+    make_variant<64, 256, 64, 1, 4, 3, kEpiSwiglu>(),
+    make_variant<256, 256, 32, 2, 4, 4, kEpiSwiglu>(),
+    make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>(),
 };
 static const GemmVariant kGemm2[] = {
-    make_variant<128, 256, 64, 2, 2, 3, false>(),
-    make_variant<256, 256, 64, 2, 2, 2, false>(),
-    make_variant<128, 512, 32, 1, 4, 3, false>(),
-    make_variant<256, 256, 64, 2, 4, 2, false>(),
-    make_variant<64, 256, 64, 1, 4, 3, false>(),
-    make_variant<256, 256, 32, 2, 4, 4, false>(),
-    make_variant<128, 256, 64, 2, 4, 3, false>(),
+    make_variant<128, 256, 64, 2, 2, 3, kEpiNone>(),
+    make_variant<256, 256, 64, 2, 2, 2, kEpiNone>(),
+    make_variant<128, 512, 32, 1, 4, 3, kEpiNone>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiNone>(),
+    make_variant<64, 256, 64, 1, 4, 3, kEpiNone>(),
+    make_variant<256, 256, 32, 2, 4, 4, kEpiNone>(),
+    make_variant<128, 256, 64, 2, 4, 3, kEpiNone>(),
 };
 constexpr int kNumVariants = sizeof(kGemm1) / sizeof(kGemm1[0]);
+// first product of the ReLU form of the FFN (default tile shape only)
+static const GemmVariant kGemm1Relu = make_variant<256, 256, 64, 2, 4, 2, kEpiRelu>();
 
 // timing hook: events recorded around the two products of the next call on this thread
 static thread_local hipEvent_t g_time_events[4];
@@ -674,17 +685,19 @@ extern "C" size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype) {
     return (size_t)3 * E * d * ffn * moegps::dtype_size(dtype);
 }
 
-extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype, int E, int d, int ffn,
-                                void* packed, void* stream) {
-    using namespace moegps;
+namespace moegps {
+// W3 == nullptr packs the ReLU form (no gate matrix): [W1 | W2] instead of [W1 W3 | W2]
+static int pack_weights_impl(const void* W1, const void* W3, const void* W2, int dtype, int E, int d, int ffn,
+                             void* packed, void* stream) {
     if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
-    if (E < 1 || d < 1 || ffn < 1 || !W1 || !W3 || !W2 || !packed) return MOE_ERR_INVALID_ARG;
+    if (E < 1 || d < 1 || ffn < 1 || !W1 || !W2 || !packed) return MOE_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     const size_t per = (size_t)E * d * ffn;
     if (dtype == MOE_DTYPE_F32) {
         if ((per * 4) % 16 != 0) return MOE_ERR_UNSUPPORTED;
-        const void* src[3] = {W1, W3, W2};
-        for (int i = 0; i < 3; ++i) {
+        const void* src[3] = {W1, W3 ? W3 : W2, W2};
+        const int n = W3 ? 3 : 2;
+        for (int i = 0; i < n; ++i) {
             hipLaunchKernelGGL(copy_u4_kernel, dim3(1024), dim3(256), 0, st, (const uint4*)src[i],
                                (uint4*)((float*)packed + i * per), per * 4 / 16);
             int rc = check_launch();
@@ -694,20 +707,42 @@ extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, 
     }
     if (d % 64 != 0 || ffn % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (E > 65535) return MOE_ERR_UNSUPPORTED;
-    bf16_t* p13 = (bf16_t*)packed;          // [E][2*ffn][d], gate/up interleaved by 32 columns
-    bf16_t* p2 = p13 + 2 * per;             // [E][d][ffn]
+    const int n1 = W3 ? 2 : 1;              // matrices in the first product
+    bf16_t* p1 = (bf16_t*)packed;           // [E][n1*ffn][d]; gate/up interleaved by 32 columns when n1 = 2
+    bf16_t* p2 = p1 + n1 * per;             // [E][d][ffn]
     const size_t es = (size_t)d * ffn;
-    // W1, W3: in[k = d][n = ffn] -> out[n'][d]
+    // W1 (, W3): in[k = d][n = ffn] -> out[n'][d]
     dim3 g13(ffn / 32, d / 32, E);
-    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p13, d, ffn, es, 2 * es, 1, 0);
+    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p1, d, ffn, es, n1 * es,
+                       W3 ? 1 : 0, 0);
     int rc = check_launch();
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p13, d, ffn, es, 2 * es, 1, 1);
-    if ((rc = check_launch()) != MOE_OK) return rc;
+    if (W3) {
+        hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p1, d, ffn, es, 2 * es, 1,
+                           1);
+        if ((rc = check_launch()) != MOE_OK) return rc;
+    }
     // W2: in[k = ffn][n = d] -> out[n = d][k = ffn]
     dim3 g2(d / 32, ffn / 32, E);
     hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, es, es, 0, 0);
     return check_launch();
+}
+}  // namespace moegps
+
+extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype, int E, int d, int ffn,
+                                void* packed, void* stream) {
+    if (!W3) return MOE_ERR_INVALID_ARG;
+    return moegps::pack_weights_impl(W1, W3, W2, dtype, E, d, ffn, packed, stream);
+}
+
+extern "C" size_t moe_packed_weights_relu_bytes(int E, int d, int ffn, int dtype) {
+    if (E < 1 || d < 1 || ffn < 1) return 0;
+    return (size_t)2 * E * d * ffn * moegps::dtype_size(dtype);
+}
+
+extern "C" int moe_pack_weights_relu(const void* W1, const void* W2, int dtype, int E, int d, int ffn, void* packed,
+                                     void* stream) {
+    return moegps::pack_weights_impl(W1, nullptr, W2, dtype, E, d, ffn, packed, stream);
 }
 
 extern "C" size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype) {
@@ -718,7 +753,7 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int
 
 namespace moegps {
 // x_perm rows are read directly (gather_rows == nullptr) or row r is x_perm[gather_rows[r] / gather_div]
-static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int gather_div, int dtype, int64_t A,
+static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_rows, int gather_div, int dtype, int64_t A,
                             int d, int ffn, int E, const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
                             int seg_begin, int seg_end, const void* packed, void* y_perm, void* workspace,
                             size_t workspace_bytes, void* stream) {
@@ -745,14 +780,20 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
         if ((rc = check_launch()) != MOE_OK) return rc;
         const float* w1 = (const float*)packed;
         const float* w3 = w1 + per;
-        const float* w2 = w3 + per;
+        const float* w2 = relu ? w3 : w3 + per;
         const int grid = 4 * num_cus();
-        hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), dim3(grid), dim3(256), 0, st, (const float*)x_perm, d, w1,
-                           w3, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts, ffn, d, gather_rows, gather_div);
+        if (relu)
+            hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), dim3(grid), dim3(256), 0, st, (const float*)x_perm, d,
+                               w1, (const float*)nullptr, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts,
+                               ffn, d, gather_rows, gather_div, 1);
+        else
+            hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), dim3(grid), dim3(256), 0, st, (const float*)x_perm, d,
+                               w1, w3, (size_t)d * ffn, (float*)ws.h, ffn, ws.tiles1, ws.counts, ffn, d, gather_rows,
+                               gather_div, 0);
         if ((rc = check_launch()) != MOE_OK) return rc;
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), dim3(grid), dim3(256), 0, st, (const float*)ws.h, ffn,
                            w2, (const float*)nullptr, (size_t)d * ffn, (float*)y_perm, d, ws.tiles1, ws.counts, d,
-                           ffn, (const int32_t*)nullptr, 1);
+                           ffn, (const int32_t*)nullptr, 1, 0);
         return check_launch();
     }
 
@@ -767,7 +808,7 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
         const int n_ntiles = ceil_div(n_cols, bn);
         return n_ntiles <= 16 ? n_ntiles : 8;
     };
-    const GemmVariant& g1 = kGemm1[v1];
+    const GemmVariant& g1 = relu ? kGemm1Relu : kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
                        E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16);
@@ -781,13 +822,14 @@ static int grouped_ffn_impl(const void* x_perm, const int32_t* gather_rows, int 
         tiles2 = ws.tiles2;
         count2 = ws.counts + 2;
     }
+    const int n1 = relu ? 1 : 2;  // matrices in the first product
     const bf16_t* p13 = (const bf16_t*)packed;
-    const bf16_t* p2 = p13 + 2 * per;
+    const bf16_t* p2 = p13 + n1 * per;
     const bool timed = g_time_armed;
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
-    rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)2 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
-                          ws.counts, ws.queues, 2 * ffn, d, group_for(2 * ffn, g1.bn), gather_rows, gather_div, st);
+    rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)n1 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
+                          ws.counts, ws.queues, n1 * ffn, d, group_for(n1 * ffn, g1.bn), gather_rows, gather_div, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
@@ -802,8 +844,16 @@ extern "C" int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, 
                                const int32_t* seg_offsets, const int32_t* slot_expert, int nseg, int seg_begin,
                                int seg_end, const void* packed, void* y_perm, void* workspace,
                                size_t workspace_bytes, void* stream) {
-    return moegps::grouped_ffn_impl(x_perm, nullptr, 1, dtype, A, d, ffn, E, seg_offsets, slot_expert, nseg, seg_begin,
-                                    seg_end, packed, y_perm, workspace, workspace_bytes, stream);
+    return moegps::grouped_ffn_impl(0, x_perm, nullptr, 1, dtype, A, d, ffn, E, seg_offsets, slot_expert, nseg,
+                                    seg_begin, seg_end, packed, y_perm, workspace, workspace_bytes, stream);
+}
+
+extern "C" int moe_grouped_ffn_relu(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
+                                    const int32_t* seg_offsets, const int32_t* slot_expert, int nseg, int seg_begin,
+                                    int seg_end, const void* packed, void* y_perm, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    return moegps::grouped_ffn_impl(1, x_perm, nullptr, 1, dtype, A, d, ffn, E, seg_offsets, slot_expert, nseg,
+                                    seg_begin, seg_end, packed, y_perm, workspace, workspace_bytes, stream);
 }
 
 extern "C" int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t* assign_of_row, int d,
@@ -813,7 +863,7 @@ extern "C" int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, co
     if (T < 0 || k < 1 || d < 1) return MOE_ERR_INVALID_ARG;
     if ((int64_t)T * d >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit element offsets into x
     if (T > 0 && !assign_of_row) return MOE_ERR_INVALID_ARG;
-    return moegps::grouped_ffn_impl(x, assign_of_row, k, dtype, (int64_t)T * k, d, ffn, E, seg_offsets, slot_expert,
+    return moegps::grouped_ffn_impl(0, x, assign_of_row, k, dtype, (int64_t)T * k, d, ffn, E, seg_offsets, slot_expert,
                                     nseg, seg_begin, seg_end, packed, y_perm, workspace, workspace_bytes, stream);
 }
 

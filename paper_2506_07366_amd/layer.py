@@ -62,9 +62,14 @@ class MoELayer:
                                   dtype=torch.uint8, device=self.dev)
         self.packed: Optional[torch.Tensor] = None
 
-    def set_weights(self, W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor) -> None:
-        """One-off repack of the (static) expert weights."""
-        self.packed = B.moe_pack_weights(W1, W3, W2)
+    def set_weights(self, W1: torch.Tensor, W3: Optional[torch.Tensor], W2: torch.Tensor) -> None:
+        """One-off repack of the (static) expert weights; the ReLU form has no W3."""
+        if self.cfg.act == "relu":
+            if self.fused_gather:
+                raise B.MoeGpsError("the fused row gather is built for the SwiGLU form only")
+            self.packed = B.moe_pack_weights_relu(W1, W2)
+        else:
+            self.packed = B.moe_pack_weights(W1, W3, W2)
 
     # individual steps (each is exactly one C-ABI call) ---------------------
     def route(self, logits):
@@ -107,7 +112,8 @@ class MoELayer:
                                      workspace=self.ws_ffn, out=self.y_perm)
         else:
             B.moe_grouped_ffn(self.perm["x_perm"], self.perm["seg_offsets"], self.slot_expert, self.packed, c.E,
-                              c.ffn, seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm)
+                              c.ffn, seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm,
+                              relu=(c.act == "relu"))
 
     def combine(self):
         c = self.cfg

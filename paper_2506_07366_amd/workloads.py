@@ -43,6 +43,7 @@ class MoEConfig:
     acc: float = 1.0       # per-token prediction accuracy (mode 2)
     seed: int = 0
     c_max: int = 0         # max copies per expert; 0 -> G
+    act: str = "swiglu"    # expert FFN form: "swiglu" (W1, W3, W2) or "relu" (W1, W2; W3 unused)
 
     @property
     def A(self) -> int:
@@ -88,6 +89,12 @@ for _ai, _alpha in enumerate((0.1, 1.0, 10.0)):
 for _mode in (MODE_NONE, MODE_DISTRIBUTION, MODE_TOKEN):
     _n = f"cfg5_decode_m{_mode}"
     CONFIGS[_n] = _cfg5(_n, 128, 1.0, _mode, seed=4)
+
+# Switch-Transformer-style layer: ReLU FFN, top-1 routing (Discussion, generality across
+# model architectures); Switch-Base widths
+CONFIGS["cfg6_switch_relu"] = MoEConfig("cfg6_switch_relu", T=16384, d=768, ffn=3072, E=64, k=1, G=8, S=10,
+                                        dtype="bf16", mode=MODE_DISTRIBUTION, alpha=0.5, sigma_pred=0.2, seed=6,
+                                        act="relu")
 
 # a mid-size bf16 case the oracle can finish in full within seconds
 CONFIGS["mid_bf16"] = MoEConfig("mid_bf16", T=512, d=512, ffn=1024, E=8, k=2, G=4, S=3,
