@@ -333,6 +333,24 @@ def main():
 
     stream = predictor_stream()
 
+    # copies-per-expert cap and slot-count sweep: the imbalance the plan alone reaches on this
+    # batch's true histogram (max planned rank load / mean), one planner call each
+    def plan_sweep():
+        H = -(-cfg.E // cfg.G)
+        rows = []
+        for S_ in sorted({H, H + 1, H + 2, min(H + 4, 16), cfg.S}):
+            if S_ < H or S_ > 16:
+                continue
+            for cm in sorted({1, 2, 4, cfg.G}):
+                if cm > cfg.G:
+                    continue
+                _, _, rl, it = B.moe_plan_duplicates(1, layer.hist, cfg.G, S_, cm)
+                rows.append({"S": S_, "c_max": cm, "imbalance": float(rl.max().item()) * cfg.G / cfg.A,
+                             "iters": int(it.item())})
+        return rows
+
+    sweep = plan_sweep()
+
     # the other row-gather variant, timed the same way (extra, not the headline; the fused
     # gather exists for the SwiGLU form only)
     other_key = "six_call_path" if args.fused_gather else "fused_gather_path"
@@ -358,7 +376,7 @@ def main():
         "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
-        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm, "predictor_stream": stream,
+        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm, "predictor_stream": stream, "plan_sweep": sweep,
         other_key: other_result,
     }
     if not args.no_cpu_baseline:

@@ -252,3 +252,30 @@ def gen_pred_idx(cfg: MoEConfig, topk_idx_true: np.ndarray) -> np.ndarray:
     keys = rng.random((cfg.T, cfg.E))
     rand_rows = np.argsort(keys, axis=1, kind="stable")[:, :cfg.k].astype(np.int32)
     return np.where(keep[:, None], idx, rand_rows).astype(np.int32)
+
+
+def gen_pred_idx_concentrated(cfg: MoEConfig, topk_idx_true: np.ndarray, target_expert: np.ndarray) -> np.ndarray:
+    """Predicted ids whose errors all fall on a chosen set of experts (the pessimistic case of
+    Section 3.3: every misprediction lands on one device when the set is that device's home
+    experts).  Rows equal the true rows except that, token by token in ascending order, the
+    entries whose true expert is in ``target_expert`` (bool [E]) are replaced by the lowest
+    expert ids that are neither in the token's true row nor already used in the row, until
+    (1 - acc) * A entries have been replaced or no such entry is left."""
+    idx = np.asarray(topk_idx_true, dtype=np.int32).reshape(cfg.T, cfg.k)
+    target = np.asarray(target_expert, dtype=bool)
+    budget = int(round((1.0 - cfg.acc) * cfg.A))
+    out = idx.copy()
+    for t in range(cfg.T):
+        if budget <= 0:
+            break
+        hit = np.nonzero(target[idx[t]])[0]
+        if hit.size == 0:
+            continue
+        free = [e for e in range(cfg.E) if e not in set(idx[t].tolist())]
+        for n, j in enumerate(hit[:budget]):
+            if n >= len(free):
+                break
+            out[t, j] = free[n]
+            budget -= 1
+    return out
+

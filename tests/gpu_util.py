@@ -30,14 +30,15 @@ def shape_key(cfg):
 class Case:
     """Host inputs + oracle results of the integer stages for one config."""
 
-    def __init__(self, cfg, with_x=True):
+    def __init__(self, cfg, with_x=True, pred_idx=None):
+        """``pred_idx``: a function of the true ids that replaces the config's own prediction."""
         self.cfg = cfg
         self.logits = wl.gen_logits(cfg)
         self.idx, self.w = route_topk(self.logits, cfg.k)
         self.hist = histogram(self.idx, cfg.E)
         self.pred_idx = None
         if cfg.mode == wl.MODE_TOKEN:
-            self.pred_idx = wl.gen_pred_idx(cfg, self.idx)
+            self.pred_idx = wl.gen_pred_idx(cfg, self.idx) if pred_idx is None else pred_idx(self.idx)
             self.hist_plan = histogram(self.pred_idx, cfg.E)
         elif cfg.mode == wl.MODE_DISTRIBUTION:
             self.hist_plan = wl.gen_pred_hist(cfg, self.hist)

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import route_topk, histogram, plan_duplicates, permute, combine
+from oracle import route_topk, histogram, plan_duplicates, permute, combine, home_slot
 from oracle.comm import comm_matrices
 from paper_2506_07366_amd import binding as B
 from paper_2506_07366_amd import workloads as wl
@@ -216,3 +216,37 @@ def test_comm_matrix_empty_batch():
     so = torch.zeros(4 * 2 + 1, dtype=torch.int32, device="cuda")
     disp, comb = B.moe_comm_matrix(0, z, None, torch.zeros(0, dtype=torch.int32, device="cuda"), so, 4, 2)
     assert int(disp.abs().sum()) == 0 and int(comb.abs().sum()) == 0
+
+
+# ---------------------------------------------------------------- pessimistic prediction errors
+def test_errors_concentrated_on_one_rank():
+    """Section 3.3, pessimistic case: every mispredicted assignment belongs to an expert homed
+    on rank 0, so all the fall-back rows pile up there.  Integers equal the oracle's, and the
+    bottleneck is worse than with the same number of errors spread at random."""
+    cfg = wl.MoEConfig("pess", T=6000, d=16, ffn=8, E=64, k=6, G=8, S=10, dtype="f32", mode=2, alpha=1.0,
+                       acc=0.85, seed=13)
+    on_rank0 = np.array([home_slot(e, cfg.E, cfg.G, cfg.S) // cfg.S == 0 for e in range(cfg.E)])
+    worst = Case(cfg, with_x=False, pred_idx=lambda idx: wl.gen_pred_idx_concentrated(cfg, idx, on_rank0))
+    typical = Case(cfg, with_x=False)
+    n_wrong = int((worst.pred_idx != worst.idx).sum())
+    assert n_wrong > 0
+
+    idx = dev_i32(worst.idx)
+    pred = dev_i32(worst.pred_idx)
+    hist = B.moe_histogram(idx, cfg.E)
+    hp = B.moe_histogram(pred, cfg.E)
+    se, sq, rl, it = B.moe_plan_duplicates(2, hp, cfg.G, cfg.S, cfg.cmax)
+    out = B.moe_permute(2, None, idx, pred, hist, hp, se, sq, cfg.E, cfg.G, cfg.S)
+    assert np.array_equal(se.cpu().numpy(), worst.plan.slot_expert)
+    assert np.array_equal(out["row_of_assign"].cpu().numpy(), worst.perm["row_of_assign"])
+    assert np.array_equal(out["rank_load"].cpu().numpy(), worst.perm["rank_load"])
+    disp, comb = B.moe_comm_matrix(2, idx, pred, out["row_of_assign"], out["seg_offsets"], cfg.G, cfg.S)
+    rdisp, rcomb = comm_matrices(2, worst.idx, worst.pred_idx, worst.perm["row_of_assign"],
+                                 worst.perm["seg_offsets"], cfg.G, cfg.S)
+    assert np.array_equal(disp.cpu().numpy(), rdisp) and np.array_equal(comb.cpu().numpy(), rcomb)
+    # every transfer at dispatch ends on rank 0
+    off = rdisp - np.diag(np.diag(rdisp))
+    assert off[:, 1:].sum() == 0 and off[:, 0].sum() > 0
+    load = worst.perm["rank_load"]
+    assert load.argmax() == 0
+    assert load.max() > typical.perm["rank_load"].max()

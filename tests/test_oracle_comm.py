@@ -141,3 +141,19 @@ def test_segment_lookup_against_a_linear_scan():
         segment_of_row(8, so)
     with pytest.raises(ValueError):
         segment_of_row(-1, so)
+
+
+def test_pessimistic_errors_all_land_on_one_rank():
+    # Section 3.3: with every misprediction on experts homed on rank 0, all dispatch transfers end there
+    cfg = wl.MoEConfig("pess", T=1500, d=16, ffn=8, E=24, k=3, G=4, S=8, dtype="f32", mode=2, alpha=1.0,
+                       acc=0.8, seed=13)
+    on0 = np.array([home_slot(e, cfg.E, cfg.G, cfg.S) // cfg.S == 0 for e in range(cfg.E)])
+    idx, pred_idx, r, disp, comb = run_case(cfg, pred_override=lambda i: wl.gen_pred_idx_concentrated(cfg, i, on0))
+    wrong = (pred_idx != idx)
+    assert wrong.sum() > 0 and np.all(on0[idx[wrong]])
+    off = disp - np.diag(np.diag(disp))
+    assert off[:, 1:].sum() == 0
+    # each wrong entry costs one row into rank 0 unless its owner is rank 0 itself
+    owners = (np.arange(cfg.T) * cfg.G) // cfg.T
+    assert off[:, 0].sum() == int((wrong & (owners[:, None] != 0)).sum())
+    assert r["rank_load"].argmax() == 0
