@@ -190,7 +190,12 @@ __device__ __forceinline__ int swz(int row) {
 // columns), kEpiRelu (max(., 0)).
 constexpr int kEpiNone = 0, kEpiSwiglu = 1, kEpiRelu = 2;
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI>
+// SCHED selects the K loop: kSchedInterleaved (every wavefront interleaves its own LDS reads
+// with its MFMAs) or kSchedAlternate (the two wavefronts of a SIMD take turns: one issues
+// only MFMAs while the other issues only memory instructions).
+constexpr int kSchedInterleaved = 0, kSchedAlternate = 1;
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
     const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
@@ -450,10 +455,92 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                 frags_landed(0);
             }
         };
-        if (tm_valid == TM)
-            k_loop(std::true_type{});
-        else
-            k_loop(std::false_type{});
+        // Alternating schedule.  The wavefronts form two groups (wm = 0, 1; wavefronts w and
+        // w + 4 share a SIMD) that run the same sequence of half-k-tile steps
+        //     memory(s): LDS -> register reads of the step's fragments (and, on the first half
+        //                of a k-tile, the global -> LDS refill of the stage freed one k-tile ago)
+        //     barrier
+        //     compute(s): the step's MFMAs, nothing else
+        //     barrier
+        // one barrier apart, so that while one group computes the other is in its memory
+        // phase.  Loads of k-tile j + 1 go out in memory(2j) and are waited for in the phase
+        // before any wavefront reads them (the end of step 2j + 1).
+        auto k_loop_alt = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            constexpr int ROW_BYTES = CPR * 16;
+            static_assert(SCHED != kSchedAlternate || (NSTAGE == 2 && BK == 64 && WGM == 2),
+                          "the alternating schedule is written for two stages of 64 and two row groups");
+            bf16x8 af[2][TM], bfr[2][TN];
+            auto load_frags = [&](int kt, int kk, int buf) {
+                const unsigned stage = lds_base + (kt & 1) * STAGE_BYTES;
+                const unsigned piece = (unsigned)(((kk * 2 + half) ^ sw) * 16);
+                static_for<TM>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    if (FULL || i < tm_valid)
+                        lds_read_b128<i * 32 * ROW_BYTES>(af[buf][i], stage + a_row * ROW_BYTES + piece);
+                });
+                static_for<TN>([&](auto J) {
+                    constexpr int j = decltype(J)::value;
+                    lds_read_b128<j * 32 * ROW_BYTES>(bfr[buf][j], stage + A_BYTES + b_row * ROW_BYTES + piece);
+                });
+            };
+            auto step = [&](int j, auto half_tag) {
+                constexpr int h = decltype(half_tag)::value;
+                // memory phase
+                if (h == 0 && j >= 1 && j + 1 < KT) issue_loads(j + 1, (j + 1) & 1);
+                load_frags(j, 2 * h, 0);
+                load_frags(j, 2 * h + 1, 1);
+                if (h == 1 && wm == 1) wait_vmcnt<0>();  // this wavefront's pieces of k-tile j + 1
+                lds_wait<0>();
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) lds_landed(af[b][i]);
+#pragma unroll
+                    for (int jj = 0; jj < TN; ++jj) lds_landed(bfr[b][jj]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_barrier();
+                // compute phase
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        if (FULL || i < tm_valid) {
+#pragma unroll
+                            for (int jj = 0; jj < TN; ++jj)
+                                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][jj], af[b][i], acc[i][jj], 0,
+                                                                                     0, 0);
+                        }
+                __builtin_amdgcn_s_setprio(0);
+                if (h == 1 && wm == 0) wait_vmcnt<0>();
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_barrier();
+            };
+            if ((!SKIP_TAIL_LOADS || mt.rows == BM) && KT >= 2)
+                wait_vmcnt<LPT>();  // k-tile 0 landed, k-tile 1 may be in flight
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            if (wm == 1) __builtin_amdgcn_s_barrier();  // the second group runs one phase behind
+            for (int j = 0; j < KT; ++j) {
+                step(j, std::integral_constant<int, 0>{});
+                step(j, std::integral_constant<int, 1>{});
+            }
+            if (wm == 0) __builtin_amdgcn_s_barrier();  // same number of barriers for both groups
+        };
+        if constexpr (SCHED == kSchedAlternate) {
+            if (tm_valid == TM)
+                k_loop_alt(std::true_type{});
+            else
+                k_loop_alt(std::false_type{});
+        } else {
+            if (tm_valid == TM)
+                k_loop(std::true_type{});
+            else
+                k_loop(std::false_type{});
+        }
         // every wavefront has read next_tile (the K loop holds a barrier)
         if (tid == 0) next_tile = settle_claim(ahead_q, ahead_i);
 
@@ -609,14 +696,14 @@ struct GemmVariant {
                  int, int, const int32_t*, int);
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved>
 static GemmVariant make_variant() {
     GemmVariant v;
     v.bm = BM;
     v.bn = BN;
     v.lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
     v.threads = WGM * WGN * 64;
-    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI>;
+    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI, SCHED>;
     return v;
 }
 
@@ -629,6 +716,7 @@ static const GemmVariant kGemm1[] = {
     make_variant<64, 256, 64, 1, 4, 3, kEpiSwiglu>(),
     make_variant<256, 256, 32, 2, 4, 4, kEpiSwiglu>(),
     make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu, kSchedAlternate>(),
 };
 static const GemmVariant kGemm2[] = {
     make_variant<128, 256, 64, 2, 2, 3, kEpiNone>(),
@@ -638,6 +726,7 @@ static const GemmVariant kGemm2[] = {
     make_variant<64, 256, 64, 1, 4, 3, kEpiNone>(),
     make_variant<256, 256, 32, 2, 4, 4, kEpiNone>(),
     make_variant<128, 256, 64, 2, 4, 3, kEpiNone>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiNone, kSchedAlternate>(),
 };
 constexpr int kNumVariants = sizeof(kGemm1) / sizeof(kGemm1[0]);
 // first product of the ReLU form of the FFN (default tile shape only)
