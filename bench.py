@@ -127,7 +127,7 @@ def main():
                          "hardware-counter run of this command holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the G expert-parallel ranks are emulated as "
+        print("bench.py: this library runs on one GPU only (the G expert-parallel ranks are emulated as "
               "partitions of one device); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -49,7 +49,7 @@ extern "C" {
 #define MOE_MODE_DISTRIBUTION  1   /* Distribution-Only Prediction, Section 3.2.1 */
 #define MOE_MODE_TOKEN         2   /* Token-to-Expert Prediction, Section 3.2.2 */
 
-/* limits of this build */
+/* compile-time limits of the library */
 #define MOE_MAX_EXPERTS   1024
 #define MOE_MAX_TOPK        16
 #define MOE_MAX_RANKS      256

@@ -10,7 +10,7 @@ extern "C" const char* moe_strerror(int code) {
     switch (code) {
         case MOE_OK: return "ok";
         case MOE_ERR_INVALID_ARG: return "invalid argument";
-        case MOE_ERR_UNSUPPORTED: return "shape or dtype not supported by this build";
+        case MOE_ERR_UNSUPPORTED: return "shape or dtype not supported by this library";
         case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MOE_ERR_HIP: return "HIP runtime error (see moe_last_hip_error)";
         default: return "unknown error code";

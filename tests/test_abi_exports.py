@@ -42,7 +42,7 @@ def test_host_side_argument_checks_need_no_gpu():
     from paper_2506_07366_amd import binding
     lib = binding.load_library()
     assert lib.moe_route_topk(None, 4, 8, 9, None, None, None) == -1          # k > E
-    assert lib.moe_route_topk(None, 4, 2000, 2, None, None, None) == -2       # E above the build limit
+    assert lib.moe_route_topk(None, 4, 2000, 2, None, None, None) == -2       # E above the compile-time limit
     assert lib.moe_route_topk(None, 0, 8, 2, None, None, None) == 0           # empty input is a no-op
     assert lib.moe_histogram(None, -1, 8, None, None) == -1
     assert lib.moe_plan_duplicates(1, None, 8, 2, 3, 2, None, None, None, None, None) == -1   # ceil(E/G) > S
