@@ -167,7 +167,8 @@ int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,
  *   packed  in  weights from moe_pack_weights
  * bf16: products accumulate in fp32, the hidden activation is rounded to bf16
  * between the two products, the output is rounded to bf16.
- * bf16 needs d % 64 == 0 and ffn % 64 == 0; f32 needs d % 4 == 0 and ffn % 4 == 0.
+ * bf16 needs d % 64 == 0 (any ffn: the packed weights pad the hidden width to a multiple
+ * of 64 with zeros); f32 needs d % 4 == 0 and ffn % 4 == 0.
  */
 size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype);
 int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,

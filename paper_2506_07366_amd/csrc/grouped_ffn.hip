@@ -37,11 +37,13 @@ struct MTile {
 // ---------------------------------------------------------------------------
 // weight packing (one-off, weights are static across inputs)
 // ---------------------------------------------------------------------------
-// out[n][k] = in[k][n] for one expert per blockIdx.z; optional interleave of the
-// output row index: rows of W1 go to (n/32)*64 + n%32, rows of W3 32 further.
+// out[n][k] = in[k][n] for one expert per blockIdx.z, zero where k >= K or n >= N (the
+// output is K_out x N_out, padded); optional interleave of the output row index: rows
+// of W1 go to (n/32)*64 + n%32, rows of W3 32 further.
 __global__ __launch_bounds__(256) void pack_transpose_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
-                                                              int K, int N, size_t in_expert_stride,
-                                                              size_t out_expert_stride, int interleave, int sel) {
+                                                              int K, int N, int K_out, int N_out,
+                                                              size_t in_expert_stride, size_t out_expert_stride,
+                                                              int interleave, int sel) {
     __shared__ bf16_t tile[32][33];
     const bf16_t* src = in + (size_t)blockIdx.z * in_expert_stride;
     bf16_t* dst = out + (size_t)blockIdx.z * out_expert_stride;
@@ -54,9 +56,9 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const bf16_t* __res
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
         const int nn = n0 + r, kk = k0 + tx;
-        if (nn < N && kk < K) {
+        if (nn < N_out && kk < K_out) {
             const int orow = interleave ? ((nn / 32) * 64 + sel * 32 + (nn % 32)) : nn;
-            dst[(size_t)orow * K + kk] = tile[tx][r];
+            dst[(size_t)orow * K_out + kk] = tile[tx][r];
         }
     }
 }
@@ -668,6 +670,13 @@ struct FfnWs {
 };
 
 constexpr int kMinBM = 64;
+
+// The bf16 kernels work on a hidden width padded to a multiple of 64: the packed weights
+// carry zero columns (W1, W3) and zero rows (W2) for the padding, so the padded hidden
+// activations are exact zeros and add nothing to the second product.
+static inline int padded_ffn(int ffn, int dtype) {
+    return dtype == MOE_DTYPE_BF16 ? (int)align_up((size_t)ffn, 64) : ffn;
+}
 constexpr int kGemmGrid = 256;  // persistent workgroups: 8 XCDs x 32
 
 static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
@@ -679,7 +688,7 @@ static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char
     };
     FfnWs w;
     w.capacity = (int)(ceil_div64(A > 0 ? A : 1, kMinBM) + nseg);
-    w.h = take((size_t)(A > 0 ? A : 1) * ffn * dtype_size(dtype));
+    w.h = take((size_t)(A > 0 ? A : 1) * padded_ffn(ffn, dtype) * dtype_size(dtype));
     w.tiles1 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.tiles2 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.counts = (int32_t*)take(256);
@@ -771,7 +780,7 @@ static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, cons
 
 extern "C" size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype) {
     if (E < 1 || d < 1 || ffn < 1) return 0;
-    return (size_t)3 * E * d * ffn * moegps::dtype_size(dtype);
+    return (size_t)3 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
 }
 
 namespace moegps {
@@ -794,26 +803,29 @@ static int pack_weights_impl(const void* W1, const void* W3, const void* W2, int
         }
         return MOE_OK;
     }
-    if (d % 64 != 0 || ffn % 64 != 0) return MOE_ERR_UNSUPPORTED;
+    if (d % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (E > 65535) return MOE_ERR_UNSUPPORTED;
+    const int fp = padded_ffn(ffn, dtype);
     const int n1 = W3 ? 2 : 1;              // matrices in the first product
-    bf16_t* p1 = (bf16_t*)packed;           // [E][n1*ffn][d]; gate/up interleaved by 32 columns when n1 = 2
-    bf16_t* p2 = p1 + n1 * per;             // [E][d][ffn]
-    const size_t es = (size_t)d * ffn;
-    // W1 (, W3): in[k = d][n = ffn] -> out[n'][d]
-    dim3 g13(ffn / 32, d / 32, E);
-    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p1, d, ffn, es, n1 * es,
-                       W3 ? 1 : 0, 0);
+    const size_t es = (size_t)d * ffn;      // one expert's matrix as given
+    const size_t ep = (size_t)d * fp;       // and padded
+    bf16_t* p1 = (bf16_t*)packed;           // [E][n1*fp][d]; gate/up interleaved by 32 columns when n1 = 2
+    bf16_t* p2 = p1 + n1 * E * ep;          // [E][d][fp]
+    // W1 (, W3): in[k = d][n = ffn] -> out[n'][d], zero rows for n >= ffn
+    dim3 g13(fp / 32, d / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p1, d, ffn, d, fp, es,
+                       n1 * ep, W3 ? 1 : 0, 0);
     int rc = check_launch();
     if (rc != MOE_OK) return rc;
     if (W3) {
-        hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p1, d, ffn, es, 2 * es, 1,
-                           1);
+        hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p1, d, ffn, d, fp, es,
+                           2 * ep, 1, 1);
         if ((rc = check_launch()) != MOE_OK) return rc;
     }
-    // W2: in[k = ffn][n = d] -> out[n = d][k = ffn]
-    dim3 g2(d / 32, ffn / 32, E);
-    hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, es, es, 0, 0);
+    // W2: in[k = ffn][n = d] -> out[n = d][k = fp], zero for k >= ffn
+    dim3 g2(d / 32, fp / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, fp, d, es, ep, 0,
+                       0);
     return check_launch();
 }
 }  // namespace moegps
@@ -826,7 +838,7 @@ extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, 
 
 extern "C" size_t moe_packed_weights_relu_bytes(int E, int d, int ffn, int dtype) {
     if (E < 1 || d < 1 || ffn < 1) return 0;
-    return (size_t)2 * E * d * ffn * moegps::dtype_size(dtype);
+    return (size_t)2 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
 }
 
 extern "C" int moe_pack_weights_relu(const void* W1, const void* W2, int dtype, int E, int d, int ffn, void* packed,
@@ -850,9 +862,9 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     if (A < 0 || d < 1 || ffn < 1 || E < 1 || nseg < 1) return MOE_ERR_INVALID_ARG;
     if (seg_begin < 0 || seg_end > nseg || seg_begin > seg_end) return MOE_ERR_INVALID_ARG;
     if (nseg > MOE_MAX_SEGMENTS || A >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
-    if (dtype == MOE_DTYPE_BF16 && (d % 64 != 0 || ffn % 64 != 0)) return MOE_ERR_UNSUPPORTED;
+    if (dtype == MOE_DTYPE_BF16 && d % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (dtype == MOE_DTYPE_F32 && (d % 4 != 0 || ffn % 4 != 0)) return MOE_ERR_UNSUPPORTED;
-    if ((int64_t)256 * (d > ffn ? d : ffn) >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit tile offsets
+    if ((int64_t)256 * (d > ffn + 63 ? d : ffn + 63) >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit tile offsets
     if (!seg_offsets || !slot_expert || !packed || !workspace) return MOE_ERR_INVALID_ARG;
     if (A > 0 && (!x_perm || !y_perm)) return MOE_ERR_INVALID_ARG;
     FfnWs ws;
@@ -912,18 +924,19 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
         count2 = ws.counts + 2;
     }
     const int n1 = relu ? 1 : 2;  // matrices in the first product
+    const int fp = padded_ffn(ffn, dtype);  // hidden width the kernels see
     const bf16_t* p13 = (const bf16_t*)packed;
-    const bf16_t* p2 = p13 + n1 * per;
+    const bf16_t* p2 = p13 + (size_t)n1 * E * d * fp;
     const bool timed = g_time_armed;
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
-    rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)n1 * d * ffn, (bf16_t*)ws.h, ffn, ws.tiles1,
-                          ws.counts, ws.queues, n1 * ffn, d, group_for(n1 * ffn, g1.bn), gather_rows, gather_div, st);
+    rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)n1 * d * fp, (bf16_t*)ws.h, fp, ws.tiles1,
+                          ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn), gather_rows, gather_div, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
-    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, ffn, p2, (size_t)d * ffn, (bf16_t*)y_perm, d, tiles2, count2,
-                          ws.queues + 8, d, ffn, group_for(d, g2.bn), nullptr, 1, st);
+    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, fp, p2, (size_t)d * fp, (bf16_t*)y_perm, d, tiles2, count2,
+                          ws.queues + 8, d, fp, group_for(d, g2.bn), nullptr, 1, st);
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
 }

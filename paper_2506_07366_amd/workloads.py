@@ -96,6 +96,11 @@ CONFIGS["cfg6_switch_relu"] = MoEConfig("cfg6_switch_relu", T=16384, d=768, ffn=
                                         dtype="bf16", mode=MODE_DISTRIBUTION, alpha=0.5, sigma_pred=0.2, seed=6,
                                         act="relu")
 
+# LLaMA-MoE-style layer (Discussion; Appendix C): SwiGLU experts cut from a dense FFN, 16
+# experts of width 11008 / 16 = 688, top-4
+CONFIGS["cfg7_llama_moe"] = MoEConfig("cfg7_llama_moe", T=8192, d=4096, ffn=688, E=16, k=4, G=8, S=3,
+                                      dtype="bf16", mode=MODE_DISTRIBUTION, alpha=0.5, sigma_pred=0.2, seed=7)
+
 # a mid-size bf16 case the oracle can finish in full within seconds
 CONFIGS["mid_bf16"] = MoEConfig("mid_bf16", T=512, d=512, ffn=1024, E=8, k=2, G=4, S=3,
                                 dtype="bf16", mode=MODE_DISTRIBUTION, alpha=0.5, sigma_pred=0.2, seed=11)

@@ -47,7 +47,8 @@ def run_ffn_case(cfg, seg_sizes, slot_expert, seed=0):
 
 
 @pytest.mark.parametrize("dtype,d,ffn", [("f32", 128, 256), ("f32", 36, 20), ("bf16", 128, 256), ("bf16", 512, 1024),
-                                         ("bf16", 64, 64), ("bf16", 192, 1408)])
+                                         ("bf16", 64, 64), ("bf16", 192, 1408), ("bf16", 128, 688), ("bf16", 64, 20),
+                                         ("bf16", 256, 1376)])
 def test_ffn_ragged_segments(dtype, d, ffn):
     E = 5
     cfg = wl.MoEConfig("f", T=1, d=d, ffn=ffn, E=E, k=1, G=4, S=3, dtype=dtype, mode=0, seed=21)
@@ -104,7 +105,7 @@ def test_layer_full_compare(name, mode):
 
 
 FULL = ["cfg2_mixtral_dist", "cfg3_mixtral_t2e", "cfg4_finegrained", "cfg5_prefill_a1_m1", "cfg5_prefill_a0.1_m2",
-        "cfg5_prefill_a10_m0", "cfg5_decode_m1", "cfg5_decode_m0", "cfg5_decode_m2", "cfg6_switch_relu"]
+        "cfg5_prefill_a10_m0", "cfg5_decode_m1", "cfg5_decode_m0", "cfg5_decode_m2", "cfg6_switch_relu", "cfg7_llama_moe"]
 
 
 @pytest.mark.parametrize("name", FULL)
@@ -246,7 +247,8 @@ def test_fused_gather_slot_range_and_oracle():
 
 # ---------------------------------------------------------------- ReLU form of the FFN
 @pytest.mark.parametrize("dtype,d,ffn", [("f32", 128, 256), ("f32", 36, 20), ("bf16", 128, 256), ("bf16", 512, 1024),
-                                         ("bf16", 64, 64), ("bf16", 768, 3072), ("bf16", 192, 1408)])
+                                         ("bf16", 64, 64), ("bf16", 768, 3072), ("bf16", 192, 1408), ("bf16", 128, 688),
+                                         ("bf16", 64, 8)])
 def test_relu_ffn_ragged_segments(dtype, d, ffn):
     E = 5
     cfg = wl.MoEConfig("f", T=1, d=d, ffn=ffn, E=E, k=1, G=4, S=3, dtype=dtype, mode=0, seed=21, act="relu")
