@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "844ed6ff1824a28b2515ad57bf9830db9b29d5cb4dffaab57c5ff2c64e0fd4e5",
-                          "fetch_bytes": 5789727397, "write_bytes": 235357286},
+    "cfg2_mixtral_dist": {"source_sha256": "5a00361bf46aecb8e688e94941de531751c4d7b2b1cf37ddba396eef18543d92",
+                          "fetch_bytes": 5751725994, "write_bytes": 235347401},
 }
 
 
