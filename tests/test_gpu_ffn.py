@@ -286,3 +286,25 @@ def test_relu_layer_top1_full_compare():
     assert rel_err(to_host_f32(out), ref["out"]) <= TOL[cfg.dtype]
     # top-1: the gate weight is exactly 1, the layer output is the expert output of the token's row
     assert np.all(case.w == 1.0)
+
+
+def test_ffn_many_tiny_segments():
+    """2048 segments (the limit) of 0..5 rows each: every M-tile is a ragged one."""
+    rng = np.random.default_rng(8)
+    E, d, ffn, nseg = 32, 64, 64, 2048
+    cfg = wl.MoEConfig("tiny", T=1, d=d, ffn=ffn, E=E, k=1, G=256, S=8, dtype="bf16", mode=0, seed=23)
+    seg_sizes = rng.integers(0, 6, size=nseg).tolist()
+    slot_expert = [int(e) if n > 0 or rng.random() < 0.5 else -1 for e, n in zip(rng.integers(0, E, size=nseg), seg_sizes)]
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=9)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
+
+
+def test_ffn_one_huge_segment_and_empty_rest():
+    """All rows in the last of 12 segments: 20 full-height tiles of one expert, nothing else."""
+    cfg = wl.MoEConfig("huge", T=1, d=128, ffn=256, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
+    seg_sizes = [0] * 11 + [5120]
+    slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 2]
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=10)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
