@@ -100,17 +100,21 @@ extern "C" int moe_combine(const void* y_perm, int dtype, int T, int d, int k, c
     if (!y_perm || !row_of_assign || !topk_w || !out) return MOE_ERR_INVALID_ARG;
     const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
     hipStream_t st = (hipStream_t)stream;
-    // few experts per token: more pieces per lane to keep enough reads in flight
-    const bool wide = (k <= 4) && chunks >= 4 * kWave;
+    // pieces per lane and step: enough 16-byte reads in flight (k * pieces) without running
+    // out of registers; rows too short for that many pieces per lane take fewer
+    int unroll = k <= 4 ? 4 : (k <= 6 ? 2 : 1);  // measured: 16 reads in flight per lane (k = 8 x 2) is slower than 8
+    while (unroll > 1 && chunks < unroll * kWave) unroll >>= 1;
     auto launch = [&](auto kern) {
         hipLaunchKernelGGL(kern, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)y_perm, row_of_assign, topk_w,
                            (uint4*)out, T, k, chunks);
     };
     if (dtype == MOE_DTYPE_BF16) {
-        if (wide) launch(combine_kernel<true, 4>);
+        if (unroll == 4) launch(combine_kernel<true, 4>);
+        else if (unroll == 2) launch(combine_kernel<true, 2>);
         else launch(combine_kernel<true, 1>);
     } else {
-        if (wide) launch(combine_kernel<false, 4>);
+        if (unroll == 4) launch(combine_kernel<false, 4>);
+        else if (unroll == 2) launch(combine_kernel<false, 2>);
         else launch(combine_kernel<false, 1>);
     }
     return check_launch();
