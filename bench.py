@@ -267,6 +267,29 @@ def main():
     }
     hbm["permute_frac"] = hbm["permute_GBs"] / PEAK_HBM_GBS
     hbm["combine_frac"] = hbm["combine_GBs"] / PEAK_HBM_GBS
+
+    # the same two stages with cold caches: a 1 GiB fill between runs pushes the operands out of
+    # the L2s and the 256 MB memory-side cache (median of 7 single runs)
+    evict = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+
+    def time_cold(fn, reps=7):
+        ts = []
+        for _ in range(reps):
+            evict.fill_(1)
+            s_, e_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s_.record()
+            fn()
+            e_.record()
+            torch.cuda.synchronize()
+            ts.append(s_.elapsed_time(e_))
+        return float(np.median(ts))
+
+    cold_p = time_cold(lambda: layer.permute(cfg.mode, x, pred_idx))
+    layer.ffn()     # y_perm of this permutation, then evicted before every combine
+    cold_c = time_cold(layer.combine)
+    del evict
+    hbm["cold"] = {"permute_ms": cold_p, "permute_GBs": bytes_permute / (cold_p * 1e-3) / 1e9,
+                   "combine_ms": cold_c, "combine_GBs": bytes_combine / (cold_c * 1e-3) / 1e9}
     report = layer.load_report()
 
     # each virtual rank's share of the FFN alone (its S slots), with and without the
