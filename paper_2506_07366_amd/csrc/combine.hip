@@ -1,8 +1,9 @@
 // Weighted un-permute: out[t] = sum_j w[t, j] * y_perm[row_of_assign[t*k + j]].
 // Stands where the all-to-all after the expert FFN is (Background: "The same
 // amount of communication happens for All-to-All shuffle after the FFN layers").
-// One wavefront per token; each lane owns 16-byte pieces of the row, gathers the
-// k source rows, accumulates in fp32 with j ascending and stores once.
+// One wavefront per token (for small batches several, each on its own slice of the
+// row); each lane owns 16-byte pieces of the row, gathers the k source rows,
+// accumulates in fp32 with j ascending and stores once.
 #include "common.h"
 
 namespace moegps {
@@ -18,10 +19,12 @@ template <bool BF16, int UNROLL>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y_perm,
                                                        const int32_t* __restrict__ row_of_assign,
                                                        const float* __restrict__ topk_w, uint4* __restrict__ out,
-                                                       int T, int k, int chunks) {
+                                                       int T, int k, int chunks, int slices) {
     typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
     const int lane = threadIdx.x & (kWave - 1);
-    const int t = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
+    // wavefront wv serves slice wv % slices of token wv / slices
+    const int wv = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
+    const int t = wv / slices, slice = wv % slices;
     if (t >= T) return;
     int rows[MOE_MAX_TOPK];
     float w[MOE_MAX_TOPK];
@@ -34,7 +37,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     constexpr int N = BF16 ? 8 : 4;
     // UNROLL 16-byte pieces per lane and step keep k * UNROLL row reads in flight; every
     // byte is touched once, so loads and stores are non-temporal
-    for (int c0 = lane; c0 < chunks; c0 += kWave * UNROLL) {
+    for (int c0 = lane + slice * kWave * UNROLL; c0 < chunks; c0 += kWave * UNROLL * slices) {
         float acc[UNROLL][N];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
@@ -104,9 +107,13 @@ extern "C" int moe_combine(const void* y_perm, int dtype, int T, int d, int k, c
     // out of registers; rows too short for that many pieces per lane take fewer
     int unroll = k <= 4 ? 4 : (k <= 6 ? 2 : 1);  // measured: 16 reads in flight per lane (k = 8 x 2) is slower than 8
     while (unroll > 1 && chunks < unroll * kWave) unroll >>= 1;
+    // a small batch leaves most of the chip idle with one wavefront per token: split the row
+    // over several wavefronts until there are a few thousand of them
+    int slices = 1;
+    while (slices < 16 && (int64_t)T * slices < 4096 && chunks >= 2 * slices * kWave * unroll) slices *= 2;
     auto launch = [&](auto kern) {
-        hipLaunchKernelGGL(kern, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)y_perm, row_of_assign, topk_w,
-                           (uint4*)out, T, k, chunks);
+        hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64((int64_t)T * slices, 4)), dim3(256), 0, st,
+                           (const uint4*)y_perm, row_of_assign, topk_w, (uint4*)out, T, k, chunks, slices);
     };
     if (dtype == MOE_DTYPE_BF16) {
         if (unroll == 4) launch(combine_kernel<true, 4>);
