@@ -357,17 +357,19 @@ template <int UNROLL>
 __global__ __launch_bounds__(256) void perm_scatter_rows_kernel(const uint4* __restrict__ x,
                                                                  uint4* __restrict__ x_perm,
                                                                  const int32_t* __restrict__ row_of_assign, int T,
-                                                                 int k, int chunks) {
+                                                                 int k, int chunks, int slices) {
     typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
     const int lane = threadIdx.x & (kWave - 1);
-    const int t = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
+    // wavefront wv serves slice wv % slices of token wv / slices (several per token only for small batches)
+    const int wv = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * (unsigned)blockDim.x + threadIdx.x) / kWave));
+    const int t = wv / slices, slice = wv % slices;
     if (t >= T) return;
     int rows[MOE_MAX_TOPK];
 #pragma unroll
     for (int j = 0; j < MOE_MAX_TOPK; ++j) rows[j] = j < k ? row_of_assign[(size_t)t * k + j] : 0;
     const u32x4* src = (const u32x4*)x + (size_t)t * chunks;
     u32x4* dst = (u32x4*)x_perm;
-    for (int c0 = lane; c0 < chunks; c0 += kWave * UNROLL) {
+    for (int c0 = lane + slice * kWave * UNROLL; c0 < chunks; c0 += kWave * UNROLL * slices) {
         u32x4 v[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
@@ -440,11 +442,15 @@ extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int
         if ((rc = check_launch()) != MOE_OK) return rc;
         if (x_perm) {
             const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
+            const int unroll = chunks >= 4 * kWave ? 4 : 1;
+            // a small batch: split every row over several wavefronts until there are a few thousand
+            int slices = 1;
+            while (slices < 16 && (int64_t)T * slices < 4096 && chunks >= 2 * slices * kWave * unroll) slices *= 2;
             auto launch = [&](auto kern) {
-                hipLaunchKernelGGL(kern, dim3(ceil_div(T, 4)), dim3(256), 0, st, (const uint4*)x, (uint4*)x_perm,
-                                   row_of_assign, T, k, chunks);
+                hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64((int64_t)T * slices, 4)), dim3(256), 0, st,
+                                   (const uint4*)x, (uint4*)x_perm, row_of_assign, T, k, chunks, slices);
             };
-            if (chunks >= 4 * kWave) launch(perm_scatter_rows_kernel<4>);
+            if (unroll == 4) launch(perm_scatter_rows_kernel<4>);
             else launch(perm_scatter_rows_kernel<1>);
             if ((rc = check_launch()) != MOE_OK) return rc;
         }
