@@ -56,7 +56,7 @@ def describe(cfg):
             f"G={cfg.G}x{cfg.S} slots, {mode} plan")
 
 
-def cpu_baseline(cfg, case_inputs, max_rows=4096):
+def cpu_baseline(cfg, case_inputs, max_rows=16384):
     """Time the oracle on the host: integer stages in full, the fp64 FFN + combine on
     whole segments holding at most ``max_rows`` rows, scaled linearly to all rows."""
     import oracle
@@ -104,7 +104,8 @@ def cpu_baseline(cfg, case_inputs, max_rows=4096):
     return {
         "value": cfg.T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
         "sample": (f"integer stages in full ({t_int:.2f} s); fp64 FFN + combine on {len(chosen)} whole segments = "
-                   f"{rows} of {cfg.A} rows ({t_ffn + t_comb:.2f} s), scaled linearly in rows (extrapolated)"),
+                   f"{rows} of {cfg.A} rows ({t_ffn + t_comb:.2f} s)"
+                   + ("" if rows >= cfg.A else ", scaled linearly in rows (extrapolated)")),
     }
 
 
