@@ -308,3 +308,17 @@ def test_ffn_one_huge_segment_and_empty_rest():
     got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=10)
     scale = np.max(np.abs(ref))
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
+
+
+@pytest.mark.parametrize("variant", range(8))
+def test_ffn_every_tile_variant(variant, monkeypatch):
+    """The tile shapes and K-loop schedules built into the library (chosen by environment
+    variable; index 3 is the default) all compute the same FFN."""
+    monkeypatch.setenv("MOEGPS_FFN_TILE1", str(variant))
+    monkeypatch.setenv("MOEGPS_FFN_TILE2", str(variant))
+    cfg = wl.MoEConfig("v", T=1, d=256, ffn=320, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
+    seg_sizes = [1, 0, 127, 129, 0, 256, 257, 63, 300, 0, 5, 64]
+    slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 0]
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=variant)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
