@@ -171,7 +171,13 @@ __device__ __forceinline__ void lds_wait() {
 }
 __device__ __forceinline__ void lds_landed(bf16x8& v) { asm volatile("" : "+v"(v)); }
 
-__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two floats rounded to bf16 (nearest even) and packed, low half first: one conversion instruction
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
 
 // silu(g) = g / (1 + exp(-g)) with the hardware reciprocal (1 ulp) in place of an IEEE division,
 // which is ten instructions per value; the result is rounded to bf16 right after.
@@ -209,7 +215,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const int32_t* __restrict__ gather_rows, int gather_div) {  // optional: A row r is A[gather_rows[r] / gather_div]
     constexpr bool SWIGLU = EPI == kEpiSwiglu;
     constexpr int NW = WGM * WGN;
-    constexpr int NT = NW * 64;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int CPR = BK / 8;                 // 16-byte pieces per tile row
@@ -573,8 +578,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                                     v[c] = acc[i][jo][g * 4 + c];
                             }
                             uint2 o;
-                            o.x = (unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16);
-                            o.y = (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16);
+                            o.x = pack_bf16x2(v[0], v[1]);
+                            o.y = pack_bf16x2(v[2], v[3]);
                             *(uint2*)(crow + jo * 32 + g * 8) = o;
                         }
                     }
@@ -681,7 +686,7 @@ static inline int padded_ffn(int ffn, int dtype) {
 }
 constexpr int kGemmGrid = 256;  // persistent workgroups: 8 XCDs x 32
 
-static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
+static size_t ffn_ws_layout(int64_t A, int /*d*/, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
         void* p = base ? (void*)(base + off) : nullptr;
