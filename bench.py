@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "85eb90bc8c430919c2677f70fd3c646002a5de4c83d1f8af39013d567f4924a6",
-                          "fetch_bytes": 5789712663, "write_bytes": 235707094},
+    "cfg2_mixtral_dist": {"source_sha256": "83fe5337a7ec33855e7b8dda6fc70e94da2f0b2bd5aa90f39f52ff83dc3dfef7",
+                          "fetch_bytes": 5766825596, "write_bytes": 235731619},
 }
 
 

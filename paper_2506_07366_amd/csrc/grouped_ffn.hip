@@ -11,9 +11,13 @@
 // as the activations, so both operands stream as K-contiguous 16-byte pieces
 // straight from global memory into LDS (global_load_lds_dwordx4) and feed
 // v_mfma_f32_32x32x16_bf16 fragments with one ds_read_b128 each.
-// A device-built table of M-tiles follows the ragged segments; workgroups walk
-// the (M-tile, N-tile) space in an order that keeps the tiles running at the
-// same time on a shared set of weight and activation panels.
+// A device-built table of M-tiles follows the ragged segments; workgroups claim
+// (M-tile, N-tile) pairs from per-XCD counters in an order that keeps the tiles
+// running at the same time on a shared set of weight and activation panels.
+// The hidden width is padded to a multiple of 64 inside the packed weights.
+//
+// The ReLU form (Discussion: Switch Transformer's FFN), y = max(x W1_e, 0) W2_e, runs
+// the same two products with another epilogue on the first.
 //
 // fp32 path (small reference-precision configs): a plain LDS-tiled FMA kernel.
 #include "common.h"
