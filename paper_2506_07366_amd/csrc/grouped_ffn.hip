@@ -909,9 +909,17 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
         return check_launch();
     }
 
-    int v1 = env_int("MOEGPS_FFN_TILE1", 3), v2 = env_int("MOEGPS_FFN_TILE2", 3);
-    if (v1 < 0 || v1 >= kNumVariants) v1 = 0;
-    if (v2 < 0 || v2 >= kNumVariants) v2 = 0;
+    // Tile shape per product: 256x256 (index 3) unless the product has too few such tiles to
+    // keep 256 workgroups busy for two rounds, then 128x256 with three stages (index 6).  The
+    // tile count is only known on the device; the host estimates it from the row count.
+    auto pick = [&](const char* env_name, int n_cols) {
+        const int v = env_int(env_name, -1);
+        if (v >= 0) return v < kNumVariants ? v : 0;
+        const int64_t est_mtiles = A / 256 + (seg_end - seg_begin + 1) / 2;
+        return est_mtiles * ceil_div(n_cols, 256) <= 2 * kGemmGrid ? 6 : 3;
+    };
+    const int v1 = pick("MOEGPS_FFN_TILE1", (relu ? 1 : 2) * padded_ffn(ffn, dtype));
+    const int v2 = pick("MOEGPS_FFN_TILE2", d);
     // N-tiles walked side by side under one run of M-tiles: all of them when the output is
     // narrow (at most 16 tiles), else 8 (measured best on the Mixtral-shaped gate/up product)
     const int group_env = env_int("MOEGPS_FFN_GROUP_N", 0);
