@@ -244,15 +244,24 @@ def main():
     stage_ms = {}
     b = 2 if bf16 else 4
 
-    def time_stage(name, fn, reps=10):
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn()
-        s.record()
-        for _ in range(reps):
+    stage_min_ms = {}
+
+    def time_stage(name, fn, reps=20):
+        """Median (and minimum) over ``reps`` single runs, each between its own pair of events
+        on the launch stream, after 5 untimed runs."""
+        for _ in range(5):
             fn()
-        e.record()
+        pairs = []
+        for _ in range(reps):
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            fn()
+            e.record()
+            pairs.append((s, e))
         torch.cuda.synchronize()
-        stage_ms[name] = s.elapsed_time(e) / reps
+        ts = [s.elapsed_time(e) for s, e in pairs]
+        stage_ms[name] = float(np.median(ts))
+        stage_min_ms[name] = float(min(ts))
 
     time_stage("route", lambda: layer.route(logits))
     time_stage("histogram", layer.histogram)
@@ -327,6 +336,7 @@ def main():
                                                         layer.perm["row_of_assign"], layer.perm["seg_offsets"],
                                                         cfg.G, cfg.S))
     comm["kernel_ms"] = stage_ms.pop("comm_matrix")
+    stage_min_ms.pop("comm_matrix")
 
     # Distribution-Only predictor over a stream of batches with one fixed expert popularity:
     # the running estimate n_i/N predicts each batch before it is seen; the plan is rebuilt
@@ -373,6 +383,8 @@ def main():
         time_stage("update", lambda: B.moe_predictor_update(batches[0][1], counts), reps=20)
         out["predict_ms"] = stage_ms.pop("predict")
         out["update_ms"] = stage_ms.pop("update")
+        stage_min_ms.pop("predict")
+        stage_min_ms.pop("update")
         return out
 
     stream = predictor_stream()
@@ -413,7 +425,7 @@ def main():
         other_result = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
 
     result.update({
-        "stage_ms": stage_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
+        "stage_ms": stage_ms, "stage_min_ms": stage_min_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
         "predictor_stream": stream, "plan_sweep": sweep,
         other_key: other_result,
     })
