@@ -325,10 +325,25 @@ extern "C" int moe_plan_duplicates(int mode, const int32_t* hist_pred, int E, in
             hipLaunchKernelGGL(kern, dim3(1), dim3(kWave), 0, st, mode, hist_pred, E, G, S, c_max, slot_expert,
                                slot_quota, rank_load_pred, n_iters);
         };
-        if (S <= 2) launch(plan_kernel_regs<2>);
-        else if (S <= 4) launch(plan_kernel_regs<4>);
-        else if (S <= 8) launch(plan_kernel_regs<8>);
-        else launch(plan_kernel_regs<16>);
+        // one instantiation per slot count: every loop over a rank's slots is unrolled to exactly S
+        switch (S) {
+            case 1: launch(plan_kernel_regs<1>); break;
+            case 2: launch(plan_kernel_regs<2>); break;
+            case 3: launch(plan_kernel_regs<3>); break;
+            case 4: launch(plan_kernel_regs<4>); break;
+            case 5: launch(plan_kernel_regs<5>); break;
+            case 6: launch(plan_kernel_regs<6>); break;
+            case 7: launch(plan_kernel_regs<7>); break;
+            case 8: launch(plan_kernel_regs<8>); break;
+            case 9: launch(plan_kernel_regs<9>); break;
+            case 10: launch(plan_kernel_regs<10>); break;
+            case 11: launch(plan_kernel_regs<11>); break;
+            case 12: launch(plan_kernel_regs<12>); break;
+            case 13: launch(plan_kernel_regs<13>); break;
+            case 14: launch(plan_kernel_regs<14>); break;
+            case 15: launch(plan_kernel_regs<15>); break;
+            default: launch(plan_kernel_regs<16>); break;
+        }
         return check_launch();
     }
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kWave), 0, st, mode, hist_pred, E, G, S, c_max, slot_expert,
