@@ -166,7 +166,10 @@ int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,
  *   seg_offsets [nseg+1], slot_expert [nseg] int32 in (device; read by the kernels)
  *   packed  in  weights from moe_pack_weights
  * bf16: products accumulate in fp32, the hidden activation is rounded to bf16
- * between the two products, the output is rounded to bf16.
+ * between the two products, the output is rounded to bf16.  When the second product has
+ * only a few tiles per workgroup, the ragged last tile of every segment is summed as two
+ * halves of the hidden width (two fp32 partial sums held in the workspace, added, then
+ * rounded once); the result does not depend on launch order.
  * bf16 needs d % 64 == 0 (any ffn: the packed weights pad the hidden width to a multiple
  * of 64 with zeros); f32 needs d % 4 == 0 and ffn % 4 == 0.
  */

@@ -35,8 +35,16 @@ struct MTile {
     int row0;    // first row of the tile in x_perm
     int rows;    // valid rows (<= BM)
     int expert;  // expert hosted by the segment's slot
-    int seg;
+    int kt0;     // k-tiles [kt0, kt1) of the product belong to this entry; kt1 == 0: all of them
+    int kt1;
+    int part;    // < 0: results go to the output; else fp32 partial sums go to slab `part`
+    int pad0, pad1;
 };
+// The ragged tile of a segment, for the pass that adds up split partial sums
+struct TailInfo {
+    int row0, rows;
+};
+constexpr int kPartRows = 256;  // rows of one slab of partial sums (the tallest tile shape)
 
 // ---------------------------------------------------------------------------
 // weight packing (one-off, weights are static across inputs)
@@ -81,11 +89,17 @@ __global__ void copy_u4_kernel(const uint4* __restrict__ in, uint4* __restrict__
 // tiles come last and fill the gaps at the end of the launch.
 // n_tiles[0] = number of tiles, n_tiles[1] = number of full-height tiles; `queues`
 // (the claim counters of the launches that walk the table) is cleared here.
+// With split_kt > 0 (the product's number of k-tiles) every ragged tile is listed twice,
+// once per half of the K range, each half writing fp32 partial sums to its own slab
+// (2 * rank + half); tails[rank] and n_tiles[2] = number of ragged tiles describe them for
+// the pass that adds the halves up.  Halving the cost of the last tiles claimed evens out
+// the end of a launch that has only a few tiles per workgroup.
 __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __restrict__ seg_offsets,
                                                              const int32_t* __restrict__ slot_expert, int seg_begin,
                                                              int seg_end, int E, int BM, MTile* __restrict__ tiles,
                                                              int capacity, int32_t* __restrict__ n_tiles,
-                                                             int32_t* __restrict__ queues, int n_queues) {
+                                                             int32_t* __restrict__ queues, int n_queues,
+                                                             int split_kt, TailInfo* __restrict__ tails) {
     __shared__ int nfull[MOE_MAX_SEGMENTS];  // full-height tiles of the segment
     __shared__ int tail[MOE_MAX_SEGMENTS];   // rows of its ragged last tile (0: none)
     __shared__ int ex[MOE_MAX_SEGMENTS];
@@ -119,7 +133,9 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         const int lo = seg_offsets[s];
         MTile mt;
         mt.expert = ex[i];
-        mt.seg = s;
+        mt.kt0 = mt.kt1 = 0;
+        mt.part = -1;
+        mt.pad0 = mt.pad1 = 0;
         for (int t = 0; t < nf; ++t) {
             if (base + t < capacity) {
                 mt.row0 = lo + t * BM;
@@ -127,16 +143,32 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
                 tiles[base + t] = mt;
             }
         }
-        if (tl > 0 && total_full + rank < capacity) {
+        if (tl > 0) {
             mt.row0 = lo + nf * BM;
             mt.rows = tl;
-            tiles[total_full + rank] = mt;
+            if (split_kt > 0) {
+                if (total_full + 2 * rank + 1 < capacity) {
+                    mt.kt0 = 0;
+                    mt.kt1 = split_kt / 2;
+                    mt.part = 2 * rank;
+                    tiles[total_full + 2 * rank] = mt;
+                    mt.kt0 = split_kt / 2;
+                    mt.kt1 = split_kt;
+                    mt.part = 2 * rank + 1;
+                    tiles[total_full + 2 * rank + 1] = mt;
+                    tails[rank].row0 = mt.row0;
+                    tails[rank].rows = tl;
+                }
+            } else if (total_full + rank < capacity) {
+                tiles[total_full + rank] = mt;
+            }
         }
     }
     if (threadIdx.x == 0) {
-        const int all = total_full + total_tail;
+        const int all = total_full + (split_kt > 0 ? 2 : 1) * total_tail;
         n_tiles[0] = all < capacity ? all : capacity;
         n_tiles[1] = total_full < capacity ? total_full : capacity;
+        if (split_kt > 0) n_tiles[2] = all <= capacity ? total_tail : 0;
     }
 }
 
@@ -216,7 +248,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     bf16_t* __restrict__ C, int ldc,                 // output [rows, SWIGLU ? N/2 : N]
     const MTile* __restrict__ mtiles, const int32_t* __restrict__ n_mtiles_ptr, int32_t* __restrict__ queues,
     int N, int K, int group_n,
-    const int32_t* __restrict__ gather_rows, int gather_div) {  // optional: A row r is A[gather_rows[r] / gather_div]
+    const int32_t* __restrict__ gather_rows, int gather_div,  // optional: A row r is A[gather_rows[r] / gather_div]
+    float* __restrict__ partials) {  // [slab][kPartRows][N] fp32 sums of tiles that cover part of K (plain product only)
     constexpr bool SWIGLU = EPI == kEpiSwiglu;
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -249,7 +282,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const int n_mtiles = n_mtiles_ptr[0];
     const int n_full = n_mtiles_ptr[1];  // the table lists these full-height tiles first
     const int n_ntiles = (N + BN - 1) / BN;
-    const int KT = K / BK;
 
     // Tile order.  The (M-tile, N-tile) space is walked in two passes, the full-height
     // M-tiles first and the ragged ones (tallest first) after them.  Inside a pass tiles
@@ -315,8 +347,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         const int n0 = nt_i * BN;
         // with a gather list the activation rows are fetched straight from their source
         // (row gather_rows[r] / gather_div of A), otherwise from row r
-        const bf16_t* Ab = gather_rows ? A : A + (size_t)mt.row0 * lda;
-        const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + (size_t)n0 * K;
+        // k-tiles of this entry: all of K, or the part of it a split tile covers
+        const int KT = mt.kt1 > 0 ? mt.kt1 - mt.kt0 : K / BK;
+        const bf16_t* Ab = (gather_rows ? A : A + (size_t)mt.row0 * lda) + mt.kt0 * BK;
+        const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + (size_t)n0 * K + mt.kt0 * BK;
         const int n_valid = (N - n0) < BN ? (N - n0) : BN;
 
         // per-lane element offsets of the pieces this lane fetches (rows beyond the
@@ -561,6 +595,34 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         const int col_w = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN)) + half * 4;
         const int n_out = SWIGLU ? N / 2 : N;
         constexpr int TNO = SWIGLU ? TN / 2 : TN;  // 32-column tiles of output per wavefront
+        if constexpr (EPI == kEpiNone) {
+            if (mt.part >= 0) {
+                // part of K only: the fp32 sums go to this entry's slab, 16 bytes per lane and group
+                float* slab = partials + (size_t)mt.part * kPartRows * N;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int row = wm * WTM + i * 32 + l32;
+                    if (row < mt.rows) {
+                        float* prow = slab + (size_t)row * N + col_w;
+#pragma unroll
+                        for (int jo = 0; jo < TN; ++jo) {
+                            if (col_w - half * 4 + jo * 32 < N) {
+#pragma unroll
+                                for (int g = 0; g < 4; ++g) {
+                                    float4 o;
+                                    o.x = acc[i][jo][g * 4 + 0];
+                                    o.y = acc[i][jo][g * 4 + 1];
+                                    o.z = acc[i][jo][g * 4 + 2];
+                                    o.w = acc[i][jo][g * 4 + 3];
+                                    *(float4*)(prow + jo * 32 + g * 8) = o;
+                                }
+                            }
+                        }
+                    }
+                }
+                continue;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = wm * WTM + i * 32 + l32;
@@ -589,6 +651,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                     }
                 }
             }
+        }
+    }
+}
+
+// Adds up the two fp32 slabs of every ragged tile whose K range was split and writes the
+// rows as bf16: y[row0 + r] = P[2t][r] + P[2t + 1][r].  blockIdx.x = ragged tile,
+// blockIdx.y strides over its rows; n_tiles[2] = number of such tiles.
+__global__ __launch_bounds__(256) void add_partials_kernel(const float* __restrict__ partials,
+                                                            const TailInfo* __restrict__ tails,
+                                                            const int32_t* __restrict__ n_tiles,
+                                                            bf16_t* __restrict__ C, int ldc, int N) {
+    const int t = blockIdx.x;
+    if (t >= n_tiles[2]) return;
+    const TailInfo ti = tails[t];
+    const float* p0 = partials + (size_t)(2 * t) * kPartRows * N;
+    const float* p1 = p0 + (size_t)kPartRows * N;
+    const int n4 = N / 4;
+    for (int r = blockIdx.y; r < ti.rows; r += gridDim.y) {
+        const float4* a = (const float4*)(p0 + (size_t)r * N);
+        const float4* b = (const float4*)(p1 + (size_t)r * N);
+        uint2* out = (uint2*)(C + (size_t)(ti.row0 + r) * ldc);
+        for (int c = threadIdx.x; c < n4; c += blockDim.x) {
+            const float4 u = a[c], v = b[c];
+            uint2 o;
+            o.x = pack_bf16x2(u.x + v.x, u.y + v.y);
+            o.y = pack_bf16x2(u.z + v.z, u.w + v.w);
+            out[c] = o;
         }
     }
 }
@@ -675,12 +764,20 @@ struct FfnWs {
     void* h;          // [A, ffn] hidden activations
     MTile* tiles1;    // M-tiles for GEMM-1
     MTile* tiles2;    // M-tiles for GEMM-2
-    int32_t* counts;  // [0..1], [2..3]: number of M-tiles and of full-height M-tiles in tiles1, tiles2
+    int32_t* counts;  // [0..1], [2..4]: number of M-tiles and of full-height M-tiles in tiles1, tiles2
+                      // (tiles2 also: number of ragged tiles listed in two halves of K)
     int32_t* queues;  // [0..7], [8..15]: per-XCD claim counters of GEMM-1, GEMM-2
+    TailInfo* tails;  // ragged tiles of the second product when their K range is split, else null
+    float* partials;  // their fp32 slabs: [2 * nseg][kPartRows][d]
     int capacity;
 };
 
 constexpr int kMinBM = 64;
+
+static int env_int(const char* name, int dflt) {
+    const char* s = getenv(name);
+    return (s && *s) ? atoi(s) : dflt;
+}
 
 // The bf16 kernels work on a hidden width padded to a multiple of 64: the packed weights
 // carry zero columns (W1, W3) and zero rows (W2) for the padding, so the padded hidden
@@ -690,7 +787,24 @@ static inline int padded_ffn(int ffn, int dtype) {
 }
 constexpr int kGemmGrid = 256;  // persistent workgroups: 8 XCDs x 32
 
-static size_t ffn_ws_layout(int64_t A, int /*d*/, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
+// The ragged tiles of the second product are computed as two halves of K (see the table
+// builder) when the product has few tiles per workgroup, so that the uneven end of the launch
+// matters, and the fp32 slabs are no larger than the hidden activations.  Decided from the sizes the
+// workspace is laid out for, so that the layout and the call agree.
+static bool split_tails(int64_t A, int d, int ffn, int nseg, int dtype) {
+    if (dtype != MOE_DTYPE_BF16 || A < 1) return false;
+    const int mode = env_int("MOEGPS_FFN_SPLIT_TAILS", 1);  // 0: never, 2: whenever the kernels can (for tests)
+    if (mode == 0) return false;
+    const int fp = padded_ffn(ffn, dtype);
+    if (fp < 128) return false;
+    if (mode == 2) return true;
+    const int64_t est_tiles = (A / 256 + (nseg + 1) / 2) * ceil_div(d, 256);
+    if (est_tiles > 4 * kGemmGrid) return false;
+    const size_t slabs = (size_t)2 * nseg * kPartRows * d * sizeof(float);
+    return slabs <= (size_t)A * fp * dtype_size(dtype);  // at most the size of the hidden activations
+}
+
+static size_t ffn_ws_layout(int64_t A, int d, int ffn, int nseg, int dtype, char* base, FfnWs* ws) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
         void* p = base ? (void*)(base + off) : nullptr;
@@ -698,22 +812,28 @@ static size_t ffn_ws_layout(int64_t A, int /*d*/, int ffn, int nseg, int dtype, 
         return p;
     };
     FfnWs w;
-    w.capacity = (int)(ceil_div64(A > 0 ? A : 1, kMinBM) + nseg);
+    w.capacity = (int)(ceil_div64(A > 0 ? A : 1, kMinBM) + 2 * nseg);
     w.h = take((size_t)(A > 0 ? A : 1) * padded_ffn(ffn, dtype) * dtype_size(dtype));
     w.tiles1 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.tiles2 = (MTile*)take((size_t)w.capacity * sizeof(MTile));
     w.counts = (int32_t*)take(256);
     w.queues = w.counts ? w.counts + 8 : nullptr;
+    w.tails = nullptr;
+    w.partials = nullptr;
+    if (split_tails(A, d, ffn, nseg, dtype)) {
+        w.tails = (TailInfo*)take((size_t)nseg * sizeof(TailInfo));
+        w.partials = (float*)take((size_t)2 * nseg * kPartRows * d * sizeof(float));
+    }
     if (ws) *ws = w;
     return off;
 }
 
 struct GemmVariant {
-    int bm, bn;
+    int bm, bn, bk;
     size_t lds;
     int threads;
     void (*kern)(const bf16_t*, int, const bf16_t*, size_t, bf16_t*, int, const MTile*, const int32_t*, int32_t*, int,
-                 int, int, const int32_t*, int);
+                 int, int, const int32_t*, int, float*);
 };
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved>
@@ -721,6 +841,7 @@ static GemmVariant make_variant() {
     GemmVariant v;
     v.bm = BM;
     v.bn = BN;
+    v.bk = BK;
     v.lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
     v.threads = WGM * WGN * 64;
     v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI, SCHED>;
@@ -756,11 +877,6 @@ static const GemmVariant kGemm1Relu = make_variant<256, 256, 64, 2, 4, 2, kEpiRe
 static thread_local hipEvent_t g_time_events[4];
 static thread_local bool g_time_armed = false;
 
-static int env_int(const char* name, int dflt) {
-    const char* s = getenv(name);
-    return (s && *s) ? atoi(s) : dflt;
-}
-
 static int num_cus() {
     static int cus = 0;
     if (cus == 0) {
@@ -775,7 +891,8 @@ static int num_cus() {
 
 static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, const bf16_t* Bp, size_t b_stride,
                             bf16_t* C, int ldc, const MTile* tiles, const int32_t* n_tiles, int32_t* queues, int N,
-                            int K, int group_n, const int32_t* gather_rows, int gather_div, hipStream_t st) {
+                            int K, int group_n, const int32_t* gather_rows, int gather_div, float* partials,
+                            hipStream_t st) {
     hipError_t e = hipFuncSetAttribute((const void*)v.kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds);
     if (e != hipSuccess) {
         set_last_hip_error(e);
@@ -783,7 +900,7 @@ static int launch_gemm_bf16(const GemmVariant& v, const bf16_t* A, int lda, cons
     }
     // 32 workgroups for each of the 8 XCDs; they claim tiles from `queues` (cleared by the table builder)
     hipLaunchKernelGGL(v.kern, dim3(kGemmGrid), dim3(v.threads), v.lds, st, A, lda, Bp, b_stride, C, ldc, tiles,
-                       n_tiles, queues, N, K, group_n, gather_rows, gather_div);
+                       n_tiles, queues, N, K, group_n, gather_rows, gather_div, partials);
     return check_launch();
 }
 
@@ -888,7 +1005,8 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
 
     if (dtype == MOE_DTYPE_F32) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
-                           seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts, (int32_t*)nullptr, 0);
+                           seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts, (int32_t*)nullptr, 0, 0,
+                           (TailInfo*)nullptr);
         if ((rc = check_launch()) != MOE_OK) return rc;
         const float* w1 = (const float*)packed;
         const float* w3 = w1 + per;
@@ -931,31 +1049,40 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     const GemmVariant& g1 = relu ? kGemm1Relu : kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
-                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16);
+                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16, 0, (TailInfo*)nullptr);
     if ((rc = check_launch()) != MOE_OK) return rc;
     const MTile* tiles2 = ws.tiles1;
     const int32_t* count2 = ws.counts;
-    if (g2.bm != g1.bm) {  // the second product walks its own M-tiles only if its tile height differs
+    const int fp = padded_ffn(ffn, dtype);  // hidden width the kernels see
+    const bool split = ws.partials != nullptr && g2.bm <= kPartRows && fp / g2.bk >= 2;
+    // the second product walks its own M-tiles only if its tile height differs or it splits ragged tiles
+    if (g2.bm != g1.bm || split) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
-                           seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 2, (int32_t*)nullptr, 0);
+                           seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 2, (int32_t*)nullptr, 0,
+                           split ? fp / g2.bk : 0, ws.tails);
         if ((rc = check_launch()) != MOE_OK) return rc;
         tiles2 = ws.tiles2;
         count2 = ws.counts + 2;
     }
     const int n1 = relu ? 1 : 2;  // matrices in the first product
-    const int fp = padded_ffn(ffn, dtype);  // hidden width the kernels see
     const bf16_t* p13 = (const bf16_t*)packed;
     const bf16_t* p2 = p13 + (size_t)n1 * E * d * fp;
     const bool timed = g_time_armed;
     g_time_armed = false;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
     rc = launch_gemm_bf16(g1, (const bf16_t*)x_perm, d, p13, (size_t)n1 * d * fp, (bf16_t*)ws.h, fp, ws.tiles1,
-                          ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn), gather_rows, gather_div, st);
+                          ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn), gather_rows, gather_div,
+                          nullptr, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
     rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, fp, p2, (size_t)d * fp, (bf16_t*)y_perm, d, tiles2, count2,
-                          ws.queues + 8, d, fp, group_for(d, g2.bn), nullptr, 1, st);
+                          ws.queues + 8, d, fp, group_for(d, g2.bn), nullptr, 1, ws.partials, st);
+    if (rc == MOE_OK && split) {
+        hipLaunchKernelGGL(add_partials_kernel, dim3(seg_end - seg_begin, 32), dim3(256), 0, st, ws.partials,
+                           ws.tails, count2, (bf16_t*)y_perm, d, d);
+        rc = check_launch();
+    }
     if (timed) (void)hipEventRecord(g_time_events[3], st);
     return rc;
 }

@@ -310,15 +310,59 @@ def test_ffn_one_huge_segment_and_empty_rest():
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
 
 
+@pytest.mark.parametrize("split", [0, 2])
 @pytest.mark.parametrize("variant", range(8))
-def test_ffn_every_tile_variant(variant, monkeypatch):
+def test_ffn_every_tile_variant(variant, split, monkeypatch):
     """The tile shapes and K-loop schedules built into the library (chosen by environment
-    variable; index 3 is the default) all compute the same FFN."""
+    variable; index 3 is the default) all compute the same FFN, with the ragged tiles of the
+    second product computed whole (0) or as two halves of K added up afterwards (2: forced;
+    320 hidden columns are 5 or 10 k-tiles, so the halves are unequal for the 64-wide ones)."""
     monkeypatch.setenv("MOEGPS_FFN_TILE1", str(variant))
     monkeypatch.setenv("MOEGPS_FFN_TILE2", str(variant))
+    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
     cfg = wl.MoEConfig("v", T=1, d=256, ffn=320, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
     seg_sizes = [1, 0, 127, 129, 0, 256, 257, 63, 300, 0, 5, 64]
     slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 0]
     got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=variant)
     scale = np.max(np.abs(ref))
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_ffn_split_tails_matches_whole_tiles(relu, monkeypatch):
+    """Ragged tiles computed as two halves of K: same result as whole tiles up to the fp32
+    association of the two partial sums (one bf16 rounding step of the output), rows of
+    full-height tiles bit-identical, and rows outside the slot range untouched."""
+    cfg = wl.MoEConfig("s", T=1, d=192, ffn=688, E=4, k=1, G=4, S=3, dtype="bf16", mode=0, seed=29)
+    rng = np.random.default_rng(31)
+    seg_sizes = [300, 0, 256, 1, 513, 0, 77, 255, 128, 0, 31, 640]
+    slot_expert = [0, -1, 2, 3, 1, 2, 0, 1, 2, -1, 3, 0]
+    A = sum(seg_sizes)
+    x = wl.quantize(rng.standard_normal((A, cfg.d)).astype(np.float32), "bf16")
+    so = np.concatenate([[0], np.cumsum(seg_sizes)]).astype(np.int32)
+    W1s, W3s, W2s = host_weights(cfg)
+    if relu:
+        packed = B.moe_pack_weights_relu(to_device(W1s, "bf16"), to_device(W2s, "bf16"))
+    else:
+        packed = B.moe_pack_weights(*dev_weights(cfg, (W1s, W3s, W2s)))
+    xd = to_device(wl.to_storage(x, "bf16"), "bf16")
+    out = {}
+    for split in (0, 2):
+        monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
+        out[split] = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn,
+                                                   relu=relu))
+        out[split, "range"] = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E,
+                                                            cfg.ffn, seg_begin=3, seg_end=8, relu=relu))
+    Wf = [wl.from_storage(w, "bf16") for w in (W1s, W3s, W2s)]
+    ref = grouped_ffn(x, so, slot_expert, Wf[0], None if relu else Wf[1], Wf[2])
+    scale = np.max(np.abs(ref))
+    for split in (0, 2):
+        assert np.all(np.max(np.abs(out[split] - ref), axis=1) <= TOL["bf16"] * scale)
+        r = out[split, "range"]
+        assert np.array_equal(r[so[3]:so[8]], out[split][so[3]:so[8]])
+        assert np.all(r[:so[3]] == 0) and np.all(r[so[8]:] == 0)
+    # the default tile height here is 128 (few tiles): rows below the last multiple of 128 of a segment are whole tiles
+    for s_ in range(len(seg_sizes)):
+        full = so[s_] + (seg_sizes[s_] // 128) * 128
+        assert np.array_equal(out[0][so[s_]:full], out[2][so[s_]:full])
+    assert np.max(np.abs(out[0] - out[2])) <= 2.0 ** -7 * scale
