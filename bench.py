@@ -301,6 +301,16 @@ def main():
     hbm["cold"] = {"permute_ms": cold_p, "permute_GBs": bytes_permute / (cold_p * 1e-3) / 1e9,
                    "combine_ms": cold_c, "combine_GBs": bytes_combine / (cold_c * 1e-3) / 1e9}
     report = layer.load_report()
+    # prediction error of this batch's inputs, to be read against the paper's Table 1:
+    # Distribution-Only: mean_e |p_hat_e - p_e| * E on the histograms; Token-to-Expert:
+    # share of (token, expert) assignments the predicted rows miss
+    if cfg.mode == 1:
+        ht, hpn = hist_true.astype(np.float64), hist_pred_h.astype(np.float64)
+        report["prediction_error"] = float(np.mean(np.abs(hpn / hpn.sum() - ht / ht.sum())) * cfg.E)
+    elif cfg.mode == 2:
+        ti = layer.topk_idx.cpu().numpy()
+        hit = (ti[:, :, None] == pred_idx_h[:, None, :]).any(axis=2)
+        report["prediction_error"] = float(1.0 - hit.mean())
 
     # each virtual rank's share of the FFN alone (its S slots), with and without the
     # duplication plan: the bottleneck rank is what expert parallelism would wait for

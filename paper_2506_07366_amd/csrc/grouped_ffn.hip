@@ -29,6 +29,7 @@ namespace moegps {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned short bf16_t;  // storage
 
 struct MTile {
@@ -99,7 +100,8 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
                                                              int seg_end, int E, int BM, MTile* __restrict__ tiles,
                                                              int capacity, int32_t* __restrict__ n_tiles,
                                                              int32_t* __restrict__ queues, int n_queues,
-                                                             int split_kt, TailInfo* __restrict__ tails) {
+                                                             int split_kt, TailInfo* __restrict__ tails,
+                                                             int inline_tails) {
     __shared__ int nfull[MOE_MAX_SEGMENTS];  // full-height tiles of the segment
     __shared__ int tail[MOE_MAX_SEGMENTS];   // rows of its ragged last tile (0: none)
     __shared__ int ex[MOE_MAX_SEGMENTS];
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         int base = 0, rank = 0;
         for (int j = 0; j < ns; ++j) {
             const bool before = ex[j] < ex[i] || (ex[j] == ex[i] && j < i);
-            if (before) base += nfull[j];
+            if (before) base += nfull[j] + ((inline_tails && tail[j] > 0) ? 1 : 0);
             if (tail[j] > tl || (tail[j] == tl && before)) ++rank;  // tail[j] > 0 whenever tl > 0 reaches here
         }
         const int s = seg_begin + i;
@@ -146,7 +148,9 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         if (tl > 0) {
             mt.row0 = lo + nf * BM;
             mt.rows = tl;
-            if (split_kt > 0) {
+            if (inline_tails) {
+                if (base + nf < capacity) tiles[base + nf] = mt;
+            } else if (split_kt > 0) {
                 if (total_full + 2 * rank + 1 < capacity) {
                     mt.kt0 = 0;
                     mt.kt1 = split_kt / 2;
@@ -165,10 +169,12 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         }
     }
     if (threadIdx.x == 0) {
-        const int all = total_full + (split_kt > 0 ? 2 : 1) * total_tail;
+        const int all = total_full + ((split_kt > 0 && !inline_tails) ? 2 : 1) * total_tail;
         n_tiles[0] = all < capacity ? all : capacity;
-        n_tiles[1] = total_full < capacity ? total_full : capacity;
-        if (split_kt > 0) n_tiles[2] = all <= capacity ? total_tail : 0;
+        // with the ragged tiles in line the whole table is one pass
+        const int first_pass = inline_tails ? all : total_full;
+        n_tiles[1] = first_pass < capacity ? first_pass : capacity;
+        if (split_kt > 0) n_tiles[2] = (all <= capacity && !inline_tails) ? total_tail : 0;
     }
 }
 
@@ -238,10 +244,15 @@ constexpr int kEpiNone = 0, kEpiSwiglu = 1, kEpiRelu = 2;
 
 // SCHED selects the K loop: kSchedInterleaved (every wavefront interleaves its own LDS reads
 // with its MFMAs) or kSchedAlternate (the two wavefronts of a SIMD take turns: one issues
-// only MFMAs while the other issues only memory instructions).
-constexpr int kSchedInterleaved = 0, kSchedAlternate = 1;
+// only MFMAs while the other issues only memory instructions), or kSchedFine (one wavefront
+// per SIMD; every memory instruction sits between two MFMAs of the same wavefront).
+constexpr int kSchedInterleaved = 0, kSchedAlternate = 1, kSchedFine = 2;
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved>
+// MI selects the matrix instruction: 32 (v_mfma_f32_32x32x16_bf16) or 16 (v_mfma_f32_16x16x32_bf16,
+// interleaved schedule only).  Both run at the same peak rate; the 16x16x32 form goes twice as
+// deep in K per accumulator read and write, and on operands with random bits -- where the chip
+// holds its clock below the maximum -- sustains about a tenth more.
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved, int MI = 32>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
     const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
@@ -373,6 +384,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             offB[i] = r * K + ((slot ^ swz<CPR>(row)) * 8);
         }
 
+        // the same offsets in bytes, unsigned: (uniform base) + (32-bit lane offset) is an addressing
+        // mode of the load instruction, so the fine schedule spends no vector ALU work on addresses
+        unsigned offA_b[IAW], offB_b[IBW];
+#pragma unroll
+        for (int i = 0; i < IAW; ++i) offA_b[i] = (unsigned)offA[i] * 2u;
+#pragma unroll
+        for (int i = 0; i < IBW; ++i) offB_b[i] = (unsigned)offB[i] * 2u;
+
         auto issue_loads = [&](int kt, int stage) {
             unsigned char* sA = smem + stage * STAGE_BYTES;
             unsigned char* sB = sA + A_BYTES;
@@ -395,13 +414,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // row operand and the activation fragment its column operand, so element r of
         // lane (l32, half) in tile (i, j) is output row i*32 + l32 and output column
         // j*32 + (r/4)*8 + half*4 + r%4: four consecutive columns per lane.
-        f32x16 acc[TM][TN];
+        f32x16 acc[MI == 32 ? TM : 1][MI == 32 ? TN : 1];
+        if constexpr (MI == 32) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        }
+        // 16x16x32 form: element r of lane (l16, g16) in tile (i, j) is output row i*16 + l16 and
+        // output column j*16 + g16*4 + r (weights are the row operand, as above)
+        constexpr int TM16 = WTM / 16, TN16 = WTN / 16;
+        f32x4 acc16[MI == 16 ? TM16 : 1][MI == 16 ? TN16 : 1];
+        if constexpr (MI == 16) {
+#pragma unroll
+            for (int i = 0; i < TM16; ++i)
+#pragma unroll
+                for (int j = 0; j < TN16; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc16[i][j][r] = 0.f;
+        }
+        const int l16 = lane & 15, g16 = lane >> 4;
 
 #pragma unroll
         for (int s = 0; s < NSTAGE; ++s)
@@ -577,7 +611,232 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             }
             if (wm == 0) __builtin_amdgcn_s_barrier();  // same number of barriers for both groups
         };
-        if constexpr (SCHED == kSchedAlternate) {
+        // Fine schedule, for one wavefront per SIMD (4 wavefronts, 128x128 each).  With nobody
+        // else on the SIMD to fill a gap, the matrix pipe only stays busy if the wavefront never
+        // spends more than one MFMA's time (32 cycles) on anything else.  So every LDS read and
+        // every global->LDS load is placed between two MFMAs: step (kt, kk) runs its 16 MFMAs
+        // and hangs the 8 fragment reads of the next step behind the first 8 of them; the last
+        // step of a k-tile starts with the hand-over (own loads of k-tile kt+1 landed, barrier),
+        // reads the first fragments of k-tile kt+1 and hangs the 16 loads of k-tile kt+2, into
+        // the stage k-tile kt just left, behind its 16 MFMAs.
+        auto k_loop_fine = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            constexpr int ROW_BYTES = CPR * 16;
+            static_assert(SCHED != kSchedFine || (NSTAGE == 2 && BK == 64 && TM * TN == 2 * IAW && IAW == IBW),
+                          "the fine schedule hangs one load behind every second MFMA of two steps");
+            bf16x8 af[2][TM], bfr[2][TN];
+            // read r of the TM + TN fragment reads of step (kt, kk), into buffer buf
+            auto read_frag = [&](auto R, int kt, int kk, int buf) {
+                constexpr int r = decltype(R)::value;
+                const unsigned stage = lds_base + (kt & 1) * STAGE_BYTES;
+                const unsigned piece = (unsigned)(((kk * 2 + half) ^ sw) * 16);
+                if constexpr (r < TM) {
+                    if (FULL || r < tm_valid)
+                        lds_read_b128<r * 32 * ROW_BYTES>(af[buf][r], stage + a_row * ROW_BYTES + piece);
+                } else {
+                    lds_read_b128<(r - TM) * 32 * ROW_BYTES>(bfr[buf][r - TM],
+                                                              stage + A_BYTES + b_row * ROW_BYTES + piece);
+                }
+            };
+            auto frags_landed = [&](int buf) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) lds_landed(af[buf][i]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) lds_landed(bfr[buf][j]);
+            };
+            // load l of the IAW + IBW loads of this wavefront for k-tile kt (l < IAW: activations)
+            auto issue_one_load = [&](auto L, int kt, int stage) {
+                constexpr int l = decltype(L)::value;
+                unsigned char* sA = smem + stage * STAGE_BYTES;
+                if constexpr (l < IAW) {
+                    const unsigned char* base = (const unsigned char*)Ab + (size_t)(kt * (BK * 2));
+                    if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void*)(base + (size_t)offA_b[l]),
+                            (__attribute__((address_space(3))) void*)(sA + (wave + l * NW) * 1024), 16, 0, 0);
+                } else {
+                    const unsigned char* base = (const unsigned char*)Bb + (size_t)(kt * (BK * 2));
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(base + (size_t)offB_b[l - IAW]),
+                        (__attribute__((address_space(3))) void*)(sA + A_BYTES + (wave + (l - IAW) * NW) * 1024), 16,
+                        0, 0);
+                }
+            };
+            // One step.  NEXT: fragments of the following step are read (false only for the very
+            // last step of the tile).  LOADS, on the last step of k-tile kt: the weight loads of
+            // k-tile kt + 2 go out here; on the first step: the activation loads of k-tile kt + 1
+            // (both into the stage that the hand-over before them has freed; the weights, which
+            // come from further away, get the longer lead).  One load behind every second MFMA.
+            auto step = [&](int kt, auto kk_tag, auto next_tag, auto loads_tag) {
+                constexpr int kk = decltype(kk_tag)::value;
+                constexpr bool NEXT = decltype(next_tag)::value, LOADS = decltype(loads_tag)::value;
+                constexpr bool LAST = kk == KK - 1;
+                constexpr int cur = kk & 1, nxt = cur ^ 1;
+                if constexpr (LAST && NEXT) {
+                    wait_vmcnt<0>();               // this wavefront's pieces of k-tile kt + 1
+                    __builtin_amdgcn_s_barrier();  // everybody's, and everybody has read all of k-tile kt
+                }
+                static_for<TM * TN>([&](auto M) {
+                    constexpr int m = decltype(M)::value;
+                    constexpr int i = m / TN, j = m % TN;
+                    if (FULL || i < tm_valid)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (NEXT && m < TM + TN) read_frag(M, LAST ? kt + 1 : kt, LAST ? 0 : kk + 1, nxt);
+                    if constexpr (LOADS && m % 2 == 1) {
+                        if constexpr (LAST)
+                            issue_one_load(std::integral_constant<int, IAW + m / 2>{}, kt + 2, kt & 1);
+                        else
+                            issue_one_load(std::integral_constant<int, m / 2>{}, kt + 1, (kt + 1) & 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                if constexpr (NEXT) {
+                    lds_wait<0>();
+                    frags_landed(nxt);
+                }
+            };
+            // a_loads: k-tile kt + 1's activations are still to be loaded (not so for kt = 0: the
+            // prologue has loaded k-tiles 0 and 1 whole); b_loads: k-tile kt + 2 exists
+            auto k_tile = [&](int kt, auto a_loads, auto b_loads) {
+                step(kt, std::integral_constant<int, 0>{}, std::true_type{}, a_loads);
+                static_for<KK - 2>([&](auto S) {
+                    step(kt, std::integral_constant<int, decltype(S)::value + 1>{}, std::true_type{}, std::false_type{});
+                });
+                step(kt, std::integral_constant<int, KK - 1>{}, std::true_type{}, b_loads);
+            };
+            if ((!SKIP_TAIL_LOADS || mt.rows == BM) && KT >= NSTAGE)
+                wait_vmcnt<LPT*(NSTAGE - 1)>();  // k-tile 0 landed, k-tile 1 may be in flight
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            static_for<TM + TN>([&](auto R) { read_frag(R, 0, 0, 0); });
+            lds_wait<0>();
+            frags_landed(0);
+            int kt = 0;
+            if (KT > 2) {
+                k_tile(0, std::false_type{}, std::true_type{});
+                for (kt = 1; kt + 2 < KT; ++kt) k_tile(kt, std::true_type{}, std::true_type{});
+                k_tile(kt, std::true_type{}, std::false_type{});  // kt = KT - 2
+                ++kt;
+            } else if (KT == 2) {
+                k_tile(0, std::false_type{}, std::false_type{});
+                kt = 1;
+            }
+            static_for<KK - 1>([&](auto S) { step(kt, S, std::true_type{}, std::false_type{}); });
+            step(kt, std::integral_constant<int, KK - 1>{}, std::false_type{}, std::false_type{});
+        };
+        // K loop of the 16x16x32 form.  A step is 32 deep: TM16 activation fragments (16 rows
+        // each) and TN16 weight fragments, TM16 * TN16 MFMAs, taken row of tiles by row of tiles.
+        // The weight fragments are double-buffered; an activation fragment is free once its row
+        // of tiles has been issued, so its register is refilled for the next step right behind
+        // that row.  LDS reads complete in issue order (weights of a step first, then its
+        // activation fragments 0, 1, ...), which fixes how many may still be in flight before
+        // each row.  The hand-over to the next k-tile (own loads landed, barrier, refill of the
+        // stage just left) sits behind the first rows of a k-tile's last step, when every
+        // fragment of that k-tile has long been read.
+        auto k_loop16 = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            constexpr int ROW_BYTES = CPR * 16;
+            constexpr int KS = BK / 32;
+            constexpr int HAND = TM16 >= 4 ? 2 : 0;  // rows of tiles issued before the hand-over
+            static_assert(MI != 16 || (CPR == 8 && KS == 2 && SCHED == kSchedInterleaved && TM16 + TN16 <= 12),
+                          "the 16x16x32 loop is written for 64-deep k-tiles and the interleaved schedule");
+            const int rows_w16 = mt.rows - wm * WTM;
+            const int tmv16 = rows_w16 <= 0 ? 0 : (rows_w16 >= WTM ? TM16 : (rows_w16 + 15) / 16);
+            const int sw16 = swz<CPR>(l16);  // rows differ by multiples of 16 -> same swizzle
+            const unsigned a_base = lds_base + (unsigned)((wm * WTM + l16) * ROW_BYTES);
+            const unsigned b_base = lds_base + (unsigned)(A_BYTES + (wn * WTN + l16) * ROW_BYTES);
+            bf16x8 af[TM16], bfr[2][TN16];
+            auto piece_of = [&](int kt, int ks) {
+                return (unsigned)((kt % NSTAGE) * STAGE_BYTES + (((ks * 4 + g16) ^ sw16) * 16));
+            };
+            auto read_a = [&](auto I, unsigned piece) {
+                constexpr int i = decltype(I)::value;
+                // read even where the rows lie past the end of a ragged tile (whatever the stage
+                // holds there: those tiles are not multiplied), so the count of reads in flight
+                // is the same for every wavefront
+                lds_read_b128<i * 16 * ROW_BYTES>(af[i], a_base + piece);
+            };
+            auto read_b_all = [&](int buf, unsigned piece) {
+                static_for<TN16>([&](auto J) {
+                    constexpr int j = decltype(J)::value;
+                    lds_read_b128<j * 16 * ROW_BYTES>(bfr[buf][j], b_base + piece);
+                });
+            };
+            auto row_mfmas = [&](auto I, int buf) {
+                constexpr int i = decltype(I)::value;
+                lds_landed(af[i]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (FULL || i < tmv16) {
+#pragma unroll
+                    for (int j = 0; j < TN16; ++j)
+                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[buf][j], af[i], acc16[i][j], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // One step.  On entry the reads of its own fragments are in flight or done, in the
+            // order weights, activation 0, 1, ...  NEXT: a step follows and its fragments are read
+            // here.  HANDOVER: this is the last step of k-tile kt and k-tile kt + 1 exists.
+            auto step = [&](int kt, auto ks_tag, auto next_tag, auto hand_tag) {
+                constexpr int ks = decltype(ks_tag)::value;
+                constexpr bool NEXT = decltype(next_tag)::value, HANDOVER = decltype(hand_tag)::value;
+                constexpr int cur = ks & 1, nxt = cur ^ 1;
+                const unsigned np = HANDOVER ? piece_of(kt + 1, 0) : piece_of(kt, ks + 1);
+                if constexpr (NEXT && !HANDOVER)
+                    lds_wait<TM16 - 1>();  // the weights and activation fragment 0 have landed
+                else
+                    lds_wait<0>();
+#pragma unroll
+                for (int j = 0; j < TN16; ++j) lds_landed(bfr[cur][j]);
+                if constexpr (NEXT && !HANDOVER) read_b_all(nxt, np);
+                static_for<TM16>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    if constexpr (HANDOVER && i == HAND) {
+                        // every fragment of k-tile kt is in a register (waited for on entry); this
+                        // wavefront's pieces of k-tile kt + 1 have landed; the barrier extends both
+                        // to every wavefront, so the stage of k-tile kt can be refilled
+                        if (KT - 2 - kt >= NSTAGE - 2)
+                            wait_vmcnt<LPT*(NSTAGE - 2)>();
+                        else
+                            wait_vmcnt<0>();
+                        __builtin_amdgcn_s_barrier();
+                        read_b_all(nxt, np);
+                        static_for<HAND>([&](auto P) { read_a(P, np); });
+                        if (kt + NSTAGE < KT) issue_loads(kt + NSTAGE, kt % NSTAGE);
+                    }
+                    if constexpr (i > 0 && NEXT && !HANDOVER)
+                        lds_wait<TM16 - 1 + TN16>();  // activation fragment i has landed
+                    row_mfmas(I, cur);
+                    if constexpr (NEXT && (!HANDOVER || i >= HAND)) read_a(I, np);
+                });
+            };
+            if ((!SKIP_TAIL_LOADS || mt.rows == BM) && KT >= NSTAGE)
+                wait_vmcnt<LPT*(NSTAGE - 1)>();  // k-tile 0 landed, the others may be in flight
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            read_b_all(0, piece_of(0, 0));
+            static_for<TM16>([&](auto I) { read_a(I, piece_of(0, 0)); });
+            int kt = 0;
+            for (; kt + 1 < KT; ++kt) {
+                step(kt, std::integral_constant<int, 0>{}, std::true_type{}, std::false_type{});
+                step(kt, std::integral_constant<int, 1>{}, std::true_type{}, std::true_type{});
+            }
+            step(kt, std::integral_constant<int, 0>{}, std::true_type{}, std::false_type{});
+            step(kt, std::integral_constant<int, 1>{}, std::false_type{}, std::false_type{});
+        };
+        if constexpr (MI == 16) {
+            if (mt.rows - wm * WTM >= WTM)
+                k_loop16(std::true_type{});
+            else
+                k_loop16(std::false_type{});
+        } else if constexpr (SCHED == kSchedFine) {
+            if (tm_valid == TM)
+                k_loop_fine(std::true_type{});
+            else
+                k_loop_fine(std::false_type{});
+        } else if constexpr (SCHED == kSchedAlternate) {
             if (tm_valid == TM)
                 k_loop_alt(std::true_type{});
             else
@@ -595,6 +854,54 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         const int col_w = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN)) + half * 4;
         const int n_out = SWIGLU ? N / 2 : N;
         constexpr int TNO = SWIGLU ? TN / 2 : TN;  // 32-column tiles of output per wavefront
+        if constexpr (MI == 16) {
+            // 4 consecutive columns per lane and tile -> 8-byte stores (16 bytes of fp32 partial sums)
+            const int n_out16 = SWIGLU ? N / 2 : N;
+            const int col0 = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN));
+            constexpr int TNO16 = SWIGLU ? TN16 / 2 : TN16;  // 16-column tiles of output per wavefront
+            static_assert(!SWIGLU || TN16 % 4 == 0, "gate and up tiles pair up inside 64 packed columns");
+            float* slab = nullptr;
+            if constexpr (EPI == kEpiNone)
+                if (mt.part >= 0) slab = partials + (size_t)mt.part * kPartRows * N;
+#pragma unroll
+            for (int i = 0; i < TM16; ++i) {
+                const int row = wm * WTM + i * 16 + l16;
+                if (row < mt.rows) {
+                    bf16_t* crow = C + (size_t)(mt.row0 + row) * ldc + col0 + g16 * 4;
+#pragma unroll
+                    for (int jo = 0; jo < TNO16; ++jo) {
+                        // output tile jo: packed tiles (jo/2)*4 + jo%2 (gate) and + 2 (up) with SwiGLU
+                        const int jg = SWIGLU ? (jo / 2) * 4 + (jo % 2) : jo;
+                        if (col0 + jo * 16 < n_out16) {
+                            float v[4];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                if (SWIGLU)
+                                    v[c] = silu_f(acc16[i][jg][c]) * acc16[i][jg + 2][c];
+                                else if (EPI == kEpiRelu)
+                                    v[c] = fmaxf(acc16[i][jg][c], 0.f);
+                                else
+                                    v[c] = acc16[i][jg][c];
+                            }
+                            if (slab) {
+                                float4 o;
+                                o.x = v[0];
+                                o.y = v[1];
+                                o.z = v[2];
+                                o.w = v[3];
+                                *(float4*)(slab + (size_t)row * N + col0 + jo * 16 + g16 * 4) = o;
+                            } else {
+                                uint2 o;
+                                o.x = pack_bf16x2(v[0], v[1]);
+                                o.y = pack_bf16x2(v[2], v[3]);
+                                *(uint2*)(crow + jo * 16) = o;
+                            }
+                        }
+                    }
+                }
+            }
+            continue;
+        }
         if constexpr (EPI == kEpiNone) {
             if (mt.part >= 0) {
                 // part of K only: the fp32 sums go to this entry's slab, 16 bytes per lane and group
@@ -836,7 +1143,7 @@ struct GemmVariant {
                  int, int, const int32_t*, int, float*);
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI, int SCHED = kSchedInterleaved, int MI = 32>
 static GemmVariant make_variant() {
     GemmVariant v;
     v.bm = BM;
@@ -844,7 +1151,7 @@ static GemmVariant make_variant() {
     v.bk = BK;
     v.lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
     v.threads = WGM * WGN * 64;
-    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI, SCHED>;
+    v.kern = grouped_gemm_bf16_kernel<BM, BN, BK, WGM, WGN, NSTAGE, EPI, SCHED, MI>;
     return v;
 }
 
@@ -858,6 +1165,9 @@ static const GemmVariant kGemm1[] = {
     make_variant<256, 256, 32, 2, 4, 4, kEpiSwiglu>(),
     make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>(),
     make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu, kSchedAlternate>(),
+    make_variant<256, 256, 64, 2, 2, 2, kEpiSwiglu, kSchedFine>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu, kSchedInterleaved, 16>(),
+    make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu, kSchedInterleaved, 16>(),
 };
 static const GemmVariant kGemm2[] = {
     make_variant<128, 256, 64, 2, 2, 3, kEpiNone>(),
@@ -868,10 +1178,13 @@ static const GemmVariant kGemm2[] = {
     make_variant<256, 256, 32, 2, 4, 4, kEpiNone>(),
     make_variant<128, 256, 64, 2, 4, 3, kEpiNone>(),
     make_variant<256, 256, 64, 2, 4, 2, kEpiNone, kSchedAlternate>(),
+    make_variant<256, 256, 64, 2, 2, 2, kEpiNone, kSchedFine>(),
+    make_variant<256, 256, 64, 2, 4, 2, kEpiNone, kSchedInterleaved, 16>(),
+    make_variant<128, 256, 64, 2, 4, 3, kEpiNone, kSchedInterleaved, 16>(),
 };
 constexpr int kNumVariants = sizeof(kGemm1) / sizeof(kGemm1[0]);
 // first product of the ReLU form of the FFN (default tile shape only)
-static const GemmVariant kGemm1Relu = make_variant<256, 256, 64, 2, 4, 2, kEpiRelu>();
+static const GemmVariant kGemm1Relu = make_variant<256, 256, 64, 2, 4, 2, kEpiRelu, kSchedInterleaved, 16>();
 
 // timing hook: events recorded around the two products of the next call on this thread
 static thread_local hipEvent_t g_time_events[4];
@@ -1006,7 +1319,7 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     if (dtype == MOE_DTYPE_F32) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
                            seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts, (int32_t*)nullptr, 0, 0,
-                           (TailInfo*)nullptr);
+                           (TailInfo*)nullptr, 0);
         if ((rc = check_launch()) != MOE_OK) return rc;
         const float* w1 = (const float*)packed;
         const float* w3 = w1 + per;
@@ -1027,14 +1340,18 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
         return check_launch();
     }
 
-    // Tile shape per product: 256x256 (index 3) unless the product has too few such tiles to
-    // keep 256 workgroups busy for two rounds, then 128x256 with three stages (index 6).  The
-    // tile count is only known on the device; the host estimates it from the row count.
+    // Tile shape per product: 256x256 (index 9) unless the product has too few such tiles to
+    // keep 256 workgroups busy for two rounds, then 128x256 with three stages (index 10); both
+    // with the 16x16x32 matrix instruction.  The tile count is only known on the device; the
+    // host estimates it from the row count.
     auto pick = [&](const char* env_name, int n_cols) {
         const int v = env_int(env_name, -1);
         if (v >= 0) return v < kNumVariants ? v : 0;
         const int64_t est_mtiles = A / 256 + (seg_end - seg_begin + 1) / 2;
-        return est_mtiles * ceil_div(n_cols, 256) <= 2 * kGemmGrid ? 6 : 3;
+        // segments of a few rows each (decode): every tile is a sliver; the low 32x32x16 tile,
+        // which skips the reads of rows that are not there, handles those fastest
+        if (A < (int64_t)64 * (seg_end - seg_begin)) return 6;
+        return est_mtiles * ceil_div(n_cols, 256) > 2 * kGemmGrid ? 9 : 10;
     };
     const int v1 = pick("MOEGPS_FFN_TILE1", (relu ? 1 : 2) * padded_ffn(ffn, dtype));
     const int v2 = pick("MOEGPS_FFN_TILE2", d);
@@ -1046,10 +1363,12 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
         const int n_ntiles = ceil_div(n_cols, bn);
         return n_ntiles <= 16 ? n_ntiles : 8;
     };
+    const int inline_tails = env_int("MOEGPS_FFN_INLINE_TAILS", 0);
     const GemmVariant& g1 = relu ? kGemm1Relu : kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
-                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16, 0, (TailInfo*)nullptr);
+                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16, 0, (TailInfo*)nullptr,
+                       inline_tails);
     if ((rc = check_launch()) != MOE_OK) return rc;
     const MTile* tiles2 = ws.tiles1;
     const int32_t* count2 = ws.counts;
@@ -1059,7 +1378,7 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     if (g2.bm != g1.bm || split) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
                            seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 2, (int32_t*)nullptr, 0,
-                           split ? fp / g2.bk : 0, ws.tails);
+                           split ? fp / g2.bk : 0, ws.tails, split ? 0 : inline_tails);
         if ((rc = check_launch()) != MOE_OK) return rc;
         tiles2 = ws.tiles2;
         count2 = ws.counts + 2;

@@ -311,7 +311,7 @@ def test_ffn_one_huge_segment_and_empty_rest():
 
 
 @pytest.mark.parametrize("split", [0, 2])
-@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("variant", range(11))
 def test_ffn_every_tile_variant(variant, split, monkeypatch):
     """The tile shapes and K-loop schedules built into the library (chosen by environment
     variable; index 3 is the default) all compute the same FFN, with the ragged tiles of the
