@@ -100,8 +100,7 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
                                                              int seg_end, int E, int BM, MTile* __restrict__ tiles,
                                                              int capacity, int32_t* __restrict__ n_tiles,
                                                              int32_t* __restrict__ queues, int n_queues,
-                                                             int split_kt, TailInfo* __restrict__ tails,
-                                                             int inline_tails) {
+                                                             int split_kt, TailInfo* __restrict__ tails) {
     __shared__ int nfull[MOE_MAX_SEGMENTS];  // full-height tiles of the segment
     __shared__ int tail[MOE_MAX_SEGMENTS];   // rows of its ragged last tile (0: none)
     __shared__ int ex[MOE_MAX_SEGMENTS];
@@ -128,7 +127,7 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         int base = 0, rank = 0;
         for (int j = 0; j < ns; ++j) {
             const bool before = ex[j] < ex[i] || (ex[j] == ex[i] && j < i);
-            if (before) base += nfull[j] + ((inline_tails && tail[j] > 0) ? 1 : 0);
+            if (before) base += nfull[j];
             if (tail[j] > tl || (tail[j] == tl && before)) ++rank;  // tail[j] > 0 whenever tl > 0 reaches here
         }
         const int s = seg_begin + i;
@@ -148,9 +147,7 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         if (tl > 0) {
             mt.row0 = lo + nf * BM;
             mt.rows = tl;
-            if (inline_tails) {
-                if (base + nf < capacity) tiles[base + nf] = mt;
-            } else if (split_kt > 0) {
+            if (split_kt > 0) {
                 if (total_full + 2 * rank + 1 < capacity) {
                     mt.kt0 = 0;
                     mt.kt1 = split_kt / 2;
@@ -169,12 +166,10 @@ __global__ __launch_bounds__(1024) void build_mtiles_kernel(const int32_t* __res
         }
     }
     if (threadIdx.x == 0) {
-        const int all = total_full + ((split_kt > 0 && !inline_tails) ? 2 : 1) * total_tail;
+        const int all = total_full + (split_kt > 0 ? 2 : 1) * total_tail;
         n_tiles[0] = all < capacity ? all : capacity;
-        // with the ragged tiles in line the whole table is one pass
-        const int first_pass = inline_tails ? all : total_full;
-        n_tiles[1] = first_pass < capacity ? first_pass : capacity;
-        if (split_kt > 0) n_tiles[2] = (all <= capacity && !inline_tails) ? total_tail : 0;
+        n_tiles[1] = total_full < capacity ? total_full : capacity;
+        if (split_kt > 0) n_tiles[2] = all <= capacity ? total_tail : 0;
     }
 }
 
@@ -1319,7 +1314,7 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     if (dtype == MOE_DTYPE_F32) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
                            seg_end, E, 64, ws.tiles1, ws.capacity, ws.counts, (int32_t*)nullptr, 0, 0,
-                           (TailInfo*)nullptr, 0);
+                           (TailInfo*)nullptr);
         if ((rc = check_launch()) != MOE_OK) return rc;
         const float* w1 = (const float*)packed;
         const float* w3 = w1 + per;
@@ -1363,12 +1358,10 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
         const int n_ntiles = ceil_div(n_cols, bn);
         return n_ntiles <= 16 ? n_ntiles : 8;
     };
-    const int inline_tails = env_int("MOEGPS_FFN_INLINE_TAILS", 0);
     const GemmVariant& g1 = relu ? kGemm1Relu : kGemm1[v1];
     const GemmVariant& g2 = kGemm2[v2];
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin, seg_end,
-                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16, 0, (TailInfo*)nullptr,
-                       inline_tails);
+                       E, g1.bm, ws.tiles1, ws.capacity, ws.counts, ws.queues, 16, 0, (TailInfo*)nullptr);
     if ((rc = check_launch()) != MOE_OK) return rc;
     const MTile* tiles2 = ws.tiles1;
     const int32_t* count2 = ws.counts;
@@ -1378,7 +1371,7 @@ static int grouped_ffn_impl(int relu, const void* x_perm, const int32_t* gather_
     if (g2.bm != g1.bm || split) {
         hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(1024), 0, st, seg_offsets, slot_expert, seg_begin,
                            seg_end, E, g2.bm, ws.tiles2, ws.capacity, ws.counts + 2, (int32_t*)nullptr, 0,
-                           split ? fp / g2.bk : 0, ws.tails, split ? 0 : inline_tails);
+                           split ? fp / g2.bk : 0, ws.tails);
         if ((rc = check_launch()) != MOE_OK) return rc;
         tiles2 = ws.tiles2;
         count2 = ws.counts + 2;
