@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "6adade048561ecb7417a2308a8fed78af239ebedc5fa3c705f6fe2270da5130f",
-                          "fetch_bytes": 5877644695, "write_bytes": 250738038},
+    "cfg2_mixtral_dist": {"source_sha256": "1c26ba12cbc5994baf1a64bc4e8c5fff67df5844bf8bb785033edefc71a0686e",
+                          "fetch_bytes": 5919402123, "write_bytes": 248770250},
 }
 
 

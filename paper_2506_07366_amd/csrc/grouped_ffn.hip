@@ -759,6 +759,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                     lds_read_b128<j * 16 * ROW_BYTES>(bfr[buf][j], b_base + piece);
                 });
             };
+            // load l of this wavefront's LPT loads of k-tile kt (activations first), one instruction
+            auto issue_load_n = [&](auto L, int kt, int stage) {
+                constexpr int l = decltype(L)::value;
+                unsigned char* sA = smem + stage * STAGE_BYTES;
+                if constexpr (l < IAW) {
+                    const unsigned char* base = (const unsigned char*)Ab + (size_t)(kt * (BK * 2));
+                    if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void*)(base + (size_t)offA_b[l]),
+                            (__attribute__((address_space(3))) void*)(sA + (wave + l * NW) * 1024), 16, 0, 0);
+                } else {
+                    const unsigned char* base = (const unsigned char*)Bb + (size_t)(kt * (BK * 2));
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(base + (size_t)offB_b[l - IAW]),
+                        (__attribute__((address_space(3))) void*)(sA + A_BYTES + (wave + (l - IAW) * NW) * 1024), 16,
+                        0, 0);
+                }
+            };
             auto row_mfmas = [&](auto I, int buf) {
                 constexpr int i = decltype(I)::value;
                 lds_landed(af[i]);
@@ -798,12 +816,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                         __builtin_amdgcn_s_barrier();
                         read_b_all(nxt, np);
                         static_for<HAND>([&](auto P) { read_a(P, np); });
-                        if (kt + NSTAGE < KT) issue_loads(kt + NSTAGE, kt % NSTAGE);
                     }
                     if constexpr (i > 0 && NEXT && !HANDOVER)
                         lds_wait<TM16 - 1 + TN16>();  // activation fragment i has landed
                     row_mfmas(I, cur);
                     if constexpr (NEXT && (!HANDOVER || i >= HAND)) read_a(I, np);
+                    if constexpr (HANDOVER && i >= HAND) {
+                        // the refill of the stage k-tile kt has left: this wavefront's loads of
+                        // k-tile kt + NSTAGE, dealt over the rows of tiles behind the hand-over so
+                        // that a load waiting for the CU's one address unit holds up a few MFMAs of
+                        // this wavefront, not the SIMD (its other wavefront keeps issuing)
+                        constexpr int R = TM16 - HAND, q = i - HAND;
+                        constexpr int l0 = q * LPT / R, l1 = (q + 1) * LPT / R;
+                        if (kt + NSTAGE < KT)
+                            static_for<l1 - l0>([&](auto D) {
+                                issue_load_n(std::integral_constant<int, l0 + decltype(D)::value>{}, kt + NSTAGE,
+                                             kt % NSTAGE);
+                            });
+                    }
                 });
             };
             if ((!SKIP_TAIL_LOADS || mt.rows == BM) && KT >= NSTAGE)
