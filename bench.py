@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "1c26ba12cbc5994baf1a64bc4e8c5fff67df5844bf8bb785033edefc71a0686e",
-                          "fetch_bytes": 5919402123, "write_bytes": 248770250},
+    "cfg2_mixtral_dist": {"source_sha256": "c75bc0feffeb4da34dd344e51698a282d4dfdea6f08941977a0bf30d5ed3199c",
+                          "fetch_bytes": 5913291838, "write_bytes": 247522231},
 }
 
 

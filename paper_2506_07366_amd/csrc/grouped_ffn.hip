@@ -10,7 +10,7 @@
 // Packed weights are stored "column-major" ([N][K], K contiguous), the same shape
 // as the activations, so both operands stream as K-contiguous 16-byte pieces
 // straight from global memory into LDS (global_load_lds_dwordx4) and feed
-// v_mfma_f32_32x32x16_bf16 fragments with one ds_read_b128 each.
+// v_mfma_f32_16x16x32_bf16 (or 32x32x16) fragments with one ds_read_b128 each.
 // A device-built table of M-tiles follows the ragged segments; workgroups claim
 // (M-tile, N-tile) pairs from per-XCD counters in an order that keeps the tiles
 // running at the same time on a shared set of weight and activation panels.
@@ -728,13 +728,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // that row.  LDS reads complete in issue order (weights of a step first, then its
         // activation fragments 0, 1, ...), which fixes how many may still be in flight before
         // each row.  The hand-over to the next k-tile (own loads landed, barrier, refill of the
-        // stage just left) sits behind the first rows of a k-tile's last step, when every
-        // fragment of that k-tile has long been read.
+        // stage just left) opens a k-tile's last step, when every fragment of that k-tile is in
+        // a register; the loads of the refill go out one or two per row of tiles.
         auto k_loop16 = [&](auto full_tag) {
             constexpr bool FULL = decltype(full_tag)::value;
             constexpr int ROW_BYTES = CPR * 16;
             constexpr int KS = BK / 32;
-            constexpr int HAND = TM16 >= 4 ? 2 : 0;  // rows of tiles issued before the hand-over
+            constexpr int HAND = 0;  // rows of tiles issued before the hand-over (0 and 1 measured alike, 2 to 4 a little slower)
             static_assert(MI != 16 || (CPR == 8 && KS == 2 && SCHED == kSchedInterleaved && TM16 + TN16 <= 12),
                           "the 16x16x32 loop is written for 64-deep k-tiles and the interleaved schedule");
             const int rows_w16 = mt.rows - wm * WTM;
@@ -1180,7 +1180,8 @@ static GemmVariant make_variant() {
     return v;
 }
 
-// tile shapes built into the library; index 0 is the default
+// tile shapes built into the library, by index; the defaults are 9, 10 and 6 (see the rule in
+// grouped_ffn_impl), the others are kept for comparison and run by the tests
 static const GemmVariant kGemm1[] = {
     make_variant<128, 256, 64, 2, 2, 3, kEpiSwiglu>(),
     make_variant<256, 256, 64, 2, 2, 2, kEpiSwiglu>(),
