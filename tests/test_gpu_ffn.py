@@ -366,3 +366,28 @@ def test_ffn_split_tails_matches_whole_tiles(relu, monkeypatch):
         full = so[s_] + (seg_sizes[s_] // 128) * 128
         assert np.array_equal(out[0][so[s_]:full], out[2][so[s_]:full])
     assert np.max(np.abs(out[0] - out[2])) <= 2.0 ** -7 * scale
+
+
+@pytest.mark.parametrize("split", [0, 2])
+def test_ffn_workspace_exact_size_accepted_one_byte_less_refused(split, monkeypatch):
+    """The size moe_grouped_ffn_workspace_bytes reports is what the call needs: a caller-owned
+    workspace of exactly that size works, one byte less is refused before anything is launched."""
+    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
+    cfg = wl.MoEConfig("w", T=1, d=128, ffn=256, E=3, k=1, G=2, S=2, dtype="bf16", mode=0, seed=33)
+    rng = np.random.default_rng(34)
+    seg_sizes = [70, 300, 0, 129]
+    slot_expert = [0, 1, -1, 2]
+    A = sum(seg_sizes)
+    x = wl.quantize(rng.standard_normal((A, cfg.d)).astype(np.float32), "bf16")
+    so = np.concatenate([[0], np.cumsum(seg_sizes)]).astype(np.int32)
+    Ws = host_weights(cfg)
+    packed = B.moe_pack_weights(*dev_weights(cfg, Ws))
+    xd = to_device(wl.to_storage(x, "bf16"), "bf16")
+    need = B.moe_grouped_ffn_workspace_bytes(A, cfg.d, cfg.ffn, len(seg_sizes), 1)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    y = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn, workspace=ws))
+    Wf = [wl.from_storage(w, "bf16") for w in Ws]
+    ref = grouped_ffn(x, so, slot_expert, *Wf)
+    assert np.all(np.max(np.abs(y - ref), axis=1) <= TOL["bf16"] * np.max(np.abs(ref)))
+    with pytest.raises(B.MoeGpsError):
+        B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn, workspace=ws[:need - 1])
