@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "c75bc0feffeb4da34dd344e51698a282d4dfdea6f08941977a0bf30d5ed3199c",
-                          "fetch_bytes": 5913291838, "write_bytes": 247522231},
+    "cfg2_mixtral_dist": {"source_sha256": "70608326d57ee485c1d04115da891052ca0da34c1b8fe32a43d0fd21fbbc1928",
+                          "fetch_bytes": 5992784827, "write_bytes": 250819485},
 }
 
 

@@ -380,7 +380,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         }
 
         // the same offsets in bytes, unsigned: (uniform base) + (32-bit lane offset) is an addressing
-        // mode of the load instruction, so the fine schedule spends no vector ALU work on addresses
+        // mode of the load instruction, so the loads spend no vector ALU work on addresses
         unsigned offA_b[IAW], offB_b[IBW];
 #pragma unroll
         for (int i = 0; i < IAW; ++i) offA_b[i] = (unsigned)offA[i] * 2u;
@@ -390,20 +390,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         auto issue_loads = [&](int kt, int stage) {
             unsigned char* sA = smem + stage * STAGE_BYTES;
             unsigned char* sB = sA + A_BYTES;
-            const bf16_t* a = Ab + kt * BK;
-            const bf16_t* b = Bb + kt * BK;
+            const unsigned char* a = (const unsigned char*)Ab + (size_t)(kt * (BK * 2));
+            const unsigned char* b = (const unsigned char*)Bb + (size_t)(kt * (BK * 2));
 #pragma unroll
             for (int i = 0; i < IAW; ++i)
                 if (!SKIP_TAIL_LOADS || (wave + i * NW) * ROWS_PER_LOAD < mt.rows)
                     __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(a + offA[i]),
+                        (const __attribute__((address_space(1))) void*)(a + (size_t)offA_b[i]),
                         (__attribute__((address_space(3))) void*)(sA + (wave + i * NW) * 1024), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < IBW; ++i)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(b + offB[i]),
+                    (const __attribute__((address_space(1))) void*)(b + (size_t)offB_b[i]),
                     (__attribute__((address_space(3))) void*)(sB + (wave + i * NW) * 1024), 16, 0, 0);
         };
+
+        // the first k-tiles are requested before the accumulators are cleared: the clearing
+        // then runs while the loads are under way
+#pragma unroll
+        for (int s = 0; s < NSTAGE; ++s)
+            if (s < KT) issue_loads(s, s);
+        __builtin_amdgcn_sched_barrier(0);
 
         // Accumulators hold the transposed product: the weight fragment is the MFMA's
         // row operand and the activation fragment its column operand, so element r of
@@ -431,10 +438,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                     for (int r = 0; r < 4; ++r) acc16[i][j][r] = 0.f;
         }
         const int l16 = lane & 15, g16 = lane >> 4;
-
-#pragma unroll
-        for (int s = 0; s < NSTAGE; ++s)
-            if (s < KT) issue_loads(s, s);
 
         // fragment read addresses (bytes inside a stage): row = base + l32, piece kk*2+half
         const int a_row = wm * WTM + l32;
