@@ -109,6 +109,55 @@ def cpu_baseline(cfg, case_inputs, max_rows=16384):
     }
 
 
+def dense_context(cfg):
+    """The dense problem behind the gate/up product, [A, d] x [d, 2*ffn] with every row on one
+    expert, run two ways over about a second each (the shader clock settles only after some
+    hundred milliseconds of load): this library's grouped GEMM on one segment (SwiGLU epilogue,
+    timed with the library's own events) and the vendor library's plain GEMM (torch.matmul ->
+    hipBLASLt, bf16 output of twice the width, no epilogue).  Random operands."""
+    import torch
+    from paper_2506_07366_amd import binding as B
+    A, d, ffn = cfg.A, cfg.d, cfg.ffn
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    mk = lambda *shape, scale=1.0: (torch.randn(shape, device="cuda", generator=g) * scale).to(torch.bfloat16)
+    x = mk(A, d)
+    W1, W3, W2 = mk(1, d, ffn, scale=0.02), mk(1, d, ffn, scale=0.02), mk(1, ffn, d, scale=0.02)
+    packed = B.moe_pack_weights(W1, W3, W2)
+    seg = torch.tensor([0, A], dtype=torch.int32, device="cuda")
+    slot = torch.tensor([0], dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.moe_grouped_ffn_workspace_bytes(A, d, ffn, 1, 1), dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(x)
+    flop = 4.0 * A * d * ffn
+    reps = max(20, int(1.0 / (flop / 1.2e15)))          # about a second at 1.2 PFLOP/s
+    run = lambda: B.moe_grouped_ffn(x, seg, slot, packed, 1, ffn, workspace=ws, out=y)
+    for _ in range(reps // 2):
+        run()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(20)]
+    for q in evs:
+        for e in q:
+            e.record()   # torch creates the underlying event at the first record
+    for q in evs:
+        B.moe_grouped_ffn_time_next_call(q)
+        run()
+    torch.cuda.synchronize()
+    own_ms = float(np.mean([q[0].elapsed_time(q[1]) for q in evs]))
+    w = torch.cat([W1[0], W3[0]], dim=1).t().contiguous()   # [2*ffn, d], K-contiguous like the packed weights
+    c = torch.empty((A, 2 * ffn), dtype=torch.bfloat16, device="cuda")
+    for _ in range(reps // 2):
+        torch.matmul(x, w.t(), out=c)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps // 2):
+        torch.matmul(x, w.t(), out=c)
+    e1.record()
+    torch.cuda.synchronize()
+    ven_ms = e0.elapsed_time(e1) / (reps // 2)
+    return {"shape": [A, 2 * ffn, d],
+            "grouped_gemm_one_segment": {"avg_ms": own_ms, "frac": flop / (own_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+            "vendor_plain_gemm": {"avg_ms": ven_ms, "frac": flop / (ven_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +172,10 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="stop after the timed steps: no per-stage, per-rank, traffic, predictor or sweep extras "
                          "(every kernel launch of the run then belongs to a whole-layer step)")
+    ap.add_argument("--dense-context", action="store_true",
+                    help="also time the gate/up product with all A rows on one expert (one segment) and the vendor "
+                         "library's plain GEMM of the same size (torch.matmul), each over about a second: context for "
+                         "the roofline figure, not part of the step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the library's plain copy kernel on 256 MiB buffers (three launches), so that a "
                          "hardware-counter run of this command holds a kernel of known traffic to scale by")
@@ -434,7 +487,12 @@ def main():
         other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         other_result = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
 
+    dense = None
+    if args.dense_context and bf16 and cfg.act != "relu":
+        dense = dense_context(cfg)
+
     result.update({
+        "dense_context": dense,
         "stage_ms": stage_ms, "stage_min_ms": stage_min_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
         "predictor_stream": stream, "plan_sweep": sweep,
         other_key: other_result,
