@@ -144,6 +144,28 @@ int moe_permute(int mode, const void* x, int dtype, int T, int d, int E, int k, 
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * moe_permute for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Arguments, outputs
+ * and limits are those of moe_permute without `workspace`/`workspace_bytes`; the counters,
+ * chunk bases and segment ids live in a fixed array of MOE_PERMUTE_STATIC_SCRATCH_BYTES that
+ * the library keeps in device memory (every GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates nothing and runs the same kernels, so its outputs are
+ * bit-identical to moe_permute's.  Sizes with
+ *     moe_permute_workspace_bytes(T, E, k, G, S) > MOE_PERMUTE_STATIC_SCRATCH_BYTES
+ * are refused with MOE_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (8 MiB holds about
+ * 1.8 million assignments at 128 experts and 160 segments).  All calls on one GPU share that GPU's array, and
+ * nothing in it needs clearing between calls (every entry a call reads it has written first);
+ * calls that overlap on one GPU -- two streams, two host threads -- race on it: serialise them.
+ */
+#define MOE_PERMUTE_STATIC_SCRATCH_BYTES (8u << 20)
+int moe_permute_static(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
+                       const int32_t* topk_idx, const int32_t* pred_idx,
+                       const int32_t* hist_true, const int32_t* hist_pred,
+                       const int32_t* slot_expert, const int32_t* slot_quota,
+                       int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                       void* x_perm, int32_t* rank_load, void* stream);
+
+/*
  * One-off repack of the expert weights into the tile order the FFN kernels
  * stream (expert weights are static across inputs, Discussion "Expert
  * duplication's communication overhead"; not part of the per-batch path).

@@ -23,7 +23,8 @@ MODE_NONE, MODE_DISTRIBUTION, MODE_TOKEN = 0, 1, 2
 
 EXPORTS = [
     "moe_strerror", "moe_last_hip_error", "moe_abi_version", "moe_route_topk", "moe_histogram",
-    "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_packed_weights_bytes",
+    "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_permute_static",
+    "moe_packed_weights_bytes",
     "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
     "moe_grouped_ffn_time_next_call",
     "moe_combine", "moe_comm_matrix", "moe_predictor_update", "moe_predictor_predict",
@@ -67,6 +68,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_permute.restype = c_int
     lib.moe_permute.argtypes = [c_int, vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
                                 vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_sz, vp]
+    lib.moe_permute_static.restype = c_int
+    lib.moe_permute_static.argtypes = lib.moe_permute.argtypes[:20] + [vp]
     lib.moe_packed_weights_bytes.restype = c_sz
     lib.moe_packed_weights_bytes.argtypes = [c_int] * 4
     lib.moe_pack_weights.restype = c_int
@@ -173,8 +176,10 @@ def moe_permute_workspace_bytes(T: int, E: int, k: int, G: int, S: int) -> int:
 def moe_permute(mode: int, x: Optional[torch.Tensor], topk_idx: torch.Tensor, pred_idx: Optional[torch.Tensor],
                 hist_true: Optional[torch.Tensor], hist_pred: Optional[torch.Tensor],
                 slot_expert: torch.Tensor, slot_quota: torch.Tensor, E: int, G: int, S: int,
-                workspace: Optional[torch.Tensor] = None, copy_rows: bool = True, out: Optional[dict] = None):
-    """Returns dict(seg_offsets, row_of_assign, assign_of_row, x_perm, rank_load)."""
+                workspace: Optional[torch.Tensor] = None, copy_rows: bool = True, out: Optional[dict] = None,
+                static_scratch: bool = False):
+    """Returns dict(seg_offsets, row_of_assign, assign_of_row, x_perm, rank_load).
+    ``static_scratch=True`` calls moe_permute_static (no workspace; pass ``out`` to allocate nothing at all)."""
     lib = load_library()
     _need(topk_idx, torch.int32, "topk_idx")
     T, k = topk_idx.shape
@@ -199,6 +204,14 @@ def moe_permute(mode: int, x: Optional[torch.Tensor], topk_idx: torch.Tensor, pr
             x_perm=(torch.empty((A, d), dtype=x.dtype, device=dev) if (x is not None and copy_rows) else None),
             rank_load=torch.empty(G, dtype=torch.int32, device=dev),
         )
+    if static_scratch:
+        # the variant that allocates nothing: scratch is the library's own fixed device array
+        _check(lib.moe_permute_static(mode, _ptr(x), dt, T, d, E, k, G, S, _ptr(topk_idx), _ptr(pred_idx),
+                                      _ptr(hist_true), _ptr(hist_pred), _ptr(slot_expert), _ptr(slot_quota),
+                                      _ptr(out["seg_offsets"]), _ptr(out["row_of_assign"]),
+                                      _ptr(out["assign_of_row"]), _ptr(out["x_perm"]), _ptr(out["rank_load"]),
+                                      _stream()), "moe_permute_static")
+        return out
     need = moe_permute_workspace_bytes(T, E, k, G, S)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)

@@ -17,6 +17,7 @@
 //   scatter  : each token row is read once and written to its k rows of x_perm
 #include "common.h"
 #include "block_scan.h"
+#include <mutex>
 
 namespace moegps {
 
@@ -392,12 +393,12 @@ extern "C" size_t moe_permute_workspace_bytes(int T, int E, int k, int G, int S)
     return perm_ws_layout(T, E, k, G, S, nullptr, nullptr);
 }
 
-extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
-                           const int32_t* topk_idx, const int32_t* pred_idx, const int32_t* hist_true,
-                           const int32_t* hist_pred, const int32_t* slot_expert, const int32_t* slot_quota,
-                           int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row, void* x_perm,
-                           int32_t* rank_load, void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace moegps;
+namespace moegps {
+static int permute_impl(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
+                        const int32_t* topk_idx, const int32_t* pred_idx, const int32_t* hist_true,
+                        const int32_t* hist_pred, const int32_t* slot_expert, const int32_t* slot_quota,
+                        int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row, void* x_perm,
+                        int32_t* rank_load, void* workspace, size_t workspace_bytes, void* stream) {
     if (mode < MOE_MODE_NONE || mode > MOE_MODE_TOKEN) return MOE_ERR_INVALID_ARG;
     if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
     if (T < 0 || d < 1 || E < 1 || k < 1 || k > E || G < 1 || S < 1) return MOE_ERR_INVALID_ARG;
@@ -456,4 +457,69 @@ extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int
         }
     }
     return MOE_OK;
+}
+}  // namespace moegps
+
+extern "C" int moe_permute(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
+                           const int32_t* topk_idx, const int32_t* pred_idx, const int32_t* hist_true,
+                           const int32_t* hist_pred, const int32_t* slot_expert, const int32_t* slot_quota,
+                           int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row, void* x_perm,
+                           int32_t* rank_load, void* workspace, size_t workspace_bytes, void* stream) {
+    return moegps::permute_impl(mode, x, dtype, T, d, E, k, G, S, topk_idx, pred_idx, hist_true, hist_pred,
+                                slot_expert, slot_quota, seg_offsets, row_of_assign, assign_of_row, x_perm, rank_load,
+                                workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------
+// The same permutation for callers that cannot allocate: the counters, chunk bases and
+// segment ids live in a fixed array in device memory that belongs to the library.
+// ---------------------------------------------------------------------------
+namespace moegps {
+static __device__ __align__(256) unsigned char scratch[MOE_PERMUTE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, looked up once
+
+// Address of this GPU's copy of the array (every GPU that loads the library holds its own,
+// at its own address).  The array's name is only a host-side handle: kernels get this pointer.
+static int static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return MOE_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_last_hip_error(e);
+            return MOE_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace moegps
+
+extern "C" int moe_permute_static(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
+                                  const int32_t* topk_idx, const int32_t* pred_idx, const int32_t* hist_true,
+                                  const int32_t* hist_pred, const int32_t* slot_expert, const int32_t* slot_quota,
+                                  int32_t* seg_offsets, int32_t* row_of_assign, int32_t* assign_of_row, void* x_perm,
+                                  int32_t* rank_load, void* stream) {
+    using namespace moegps;
+    if (T < 0 || E < 1 || k < 1 || G < 1 || S < 1) return MOE_ERR_INVALID_ARG;
+    // sizes whose counters do not fit the fixed array are refused before anything is enqueued
+    if (perm_ws_layout(T, E, k, G, S, nullptr, nullptr) > (size_t)MOE_PERMUTE_STATIC_SCRATCH_BYTES)
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != MOE_OK) return rc;
+    return permute_impl(mode, x, dtype, T, d, E, k, G, S, topk_idx, pred_idx, hist_true, hist_pred, slot_expert,
+                        slot_quota, seg_offsets, row_of_assign, assign_of_row, x_perm, rank_load, ptr,
+                        (size_t)MOE_PERMUTE_STATIC_SCRATCH_BYTES, stream);
 }
