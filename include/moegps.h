@@ -109,8 +109,8 @@ int moe_plan_duplicates(int mode, const int32_t* hist_pred, int E, int G, int S,
 
 /*
  * Dispatch + permutation (the dispatch d of Algorithm 1; stands where the
- * all-to-all before the expert FFN is, Background "Routing incurs inter-device
- * communication").  Every assignment gets a segment:
+ * all-to-all before the expert FFN is; Background, paragraph on the communication
+ * cost of routing).  Every assignment gets a segment:
  *   mode 0: the home slot of its expert;
  *   mode 1: replicas of expert e in ascending slot id take contiguous ranges of
  *           e's assignments (ascending a) with boundaries floor(n_e*Q_r/nhat_e),
@@ -187,13 +187,17 @@ int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,
  *   x_perm [A, d] dtype in;  y_perm [A, d] dtype out
  *   seg_offsets [nseg+1], slot_expert [nseg] int32 in (device; read by the kernels)
  *   packed  in  weights from moe_pack_weights
- * bf16: products accumulate in fp32, the hidden activation is rounded to bf16
- * between the two products, the output is rounded to bf16.  When the second product has
- * only a few tiles per workgroup, the ragged last tile of every segment is summed as two
- * halves of the hidden width (two fp32 partial sums held in the workspace, added, then
- * rounded once); the result does not depend on launch order.
- * bf16 needs d % 64 == 0 (any ffn: the packed weights pad the hidden width to a multiple
- * of 64 with zeros); f32 needs d % 4 == 0 and ffn % 4 == 0.
+ * Rows are tiled by expert: the rows of all segments of the range that host one expert are
+ * multiplied under that expert's weight panels together (replicas hold the same weights), so
+ * the result of a row depends on its values and its expert only.
+ * bf16: products accumulate in fp32, the hidden activation is rounded to bf16 between the
+ * two products, the output is rounded to bf16.  SwiGLU uses the hardware exponential and
+ * reciprocal instructions (about 1 ulp each, far below the bf16 rounding that follows).
+ * When the second product has only a few tiles per workgroup, its closing tiles are summed as
+ * up to four parts of the hidden width (fp32 partial sums held in the workspace, added in the
+ * order of the parts, then rounded once); the result does not depend on launch order.
+ * bf16 needs d % 64 == 0 (any ffn: the packed weights pad the hidden width to a multiple of
+ * 64 with zeros) and A * d < 2^31; f32 needs d % 4 == 0 and ffn % 4 == 0.
  */
 size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype);
 int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
@@ -202,19 +206,45 @@ int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, in
                     void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Same FFN, but the activation rows are gathered inside the first product instead
- * of being read from a permuted copy: row r of the (virtual) x_perm is
- * x[assign_of_row[r] / k].  moe_permute can then be called with x_perm = NULL, which
- * removes one write and one read of A*d elements from the layer.  Output and
- * numerics are those of moe_grouped_ffn on the copied rows.
- *   x [T, d] dtype in;  assign_of_row [T*k] int32 in (from moe_permute)
+ * Same FFN with the boundary copies folded in.  The activation rows are gathered inside the
+ * first product instead of being read from a permuted copy: row r of the (virtual) x_perm is
+ * x[assign_of_row[r] / k], so moe_permute can be called with x_perm = NULL, which removes one
+ * write and one read of A*d elements from the layer.  With topk_w != NULL the second product
+ * also multiplies row r of its result by the gate weight of its assignment,
+ * topk_w[assign_of_row[r]], in fp32 before the row is rounded; moe_combine is then called with
+ * topk_w = NULL and only adds the k rows of a token (the weighted sum of the return
+ * all-to-all, Background, moved in front of the transfer).  moe_grouped_ffn_gather is the call
+ * without gate weights: its output and numerics are those of moe_grouped_ffn on the copied rows.
+ *   x [T, d] dtype in;  assign_of_row [T*k] int32 in (from moe_permute);
+ *   topk_w [T, k] float in or NULL
  * The other arguments are those of moe_grouped_ffn with A = T*k.  T*d < 2^31.
  */
+int moe_grouped_ffn_fused(const void* x, int dtype, int T, int k, const int32_t* assign_of_row,
+                          const float* topk_w, int d, int ffn, int E,
+                          const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
+                          int seg_begin, int seg_end, const void* packed,
+                          void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t* assign_of_row,
                            int d, int ffn, int E,
                            const int32_t* seg_offsets, const int32_t* slot_expert, int nseg,
                            int seg_begin, int seg_end, const void* packed,
                            void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Overrides of the automatic choices inside the grouped FFN, for tests and experiments
+ * (process-wide; set them before sizing a workspace, the split option changes its size):
+ *   MOE_FFN_OPT_TILE1 / TILE2  tile shape of the first / second product: -1 automatic,
+ *                              0 = 256x256x64, 1 = 128x256x64
+ *   MOE_FFN_OPT_SPLIT_K        closing tiles of the second product as parts of K:
+ *                              -1 automatic, 0 never, 1 whenever the shapes allow
+ *   MOE_FFN_OPT_GROUP_N        N-tiles walked side by side under one run of M-tiles, 0 automatic
+ * Returns MOE_ERR_INVALID_ARG for an unknown option or a value out of range.
+ */
+#define MOE_FFN_OPT_TILE1    0
+#define MOE_FFN_OPT_TILE2    1
+#define MOE_FFN_OPT_SPLIT_K  2
+#define MOE_FFN_OPT_GROUP_N  3
+int moe_grouped_ffn_set_option(int option, int value);
 
 /*
  * The ReLU form of the expert FFN (Discussion, "Generality across model architectures":
@@ -235,10 +265,11 @@ int moe_grouped_ffn_relu(const void* x_perm, int dtype, int64_t A, int d, int ff
                          void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Optional timing hook for the next moe_grouped_ffn / moe_grouped_ffn_gather call on this host thread:
+ * Optional timing hook for the next moe_grouped_ffn* call on this host thread:
  * events[0..3] are hipEvent_t handles (as void*) that the call records on its
  * stream before and after its first product (gate/up + SwiGLU) and before and
- * after its second product (down).  The hook is consumed by that one call.
+ * after its second product (down).  The hook is consumed by that one call, also when the
+ * call returns early or takes the fp32 path (which records nothing).
  * Pass NULL to clear it.  `events` is a HOST array of 4 handles; it is copied.
  */
 int moe_grouped_ffn_time_next_call(void* const* events);
@@ -249,13 +280,15 @@ int moe_grouped_ffn_time_next_call(void* const* events);
  * summed in fp32 with j ascending; bf16 output is rounded once at the end.
  *   y_perm [A, d] dtype in, row_of_assign [A] int32 in, topk_w [T, k] float in,
  *   out [T, d] dtype out.  d * sizeof(dtype) must be a multiple of 16.
+ * topk_w = NULL adds the k rows unweighted (rows that moe_grouped_ffn_fused has already
+ * multiplied by their gate weights).
  */
 int moe_combine(const void* y_perm, int dtype, int T, int d, int k,
                 const int32_t* row_of_assign, const float* topk_w, void* out, void* stream);
 
 /*
- * Rows that cross the emulated expert-parallel ranks (Background, "Routing incurs
- * inter-device communication": with N ranks and a balanced distribution (N-1)/N of a
+ * Rows that cross the emulated expert-parallel ranks (Background, paragraph on the
+ * communication cost of routing: with N ranks and a balanced distribution (N-1)/N of a
  * rank's rows leave it and the rank of the most popular expert receives skewness times
  * the average; the all-to-all after the FFN moves the same rows back.  Section 3.2.2:
  * under Token-to-Expert prediction a correctly predicted token is already on the rank of

@@ -1,8 +1,8 @@
 """Oracle: exhaustive replica assignment on tiny E / G (test infrastructure, CPU only).
 
 Quality bound for the greedy planner of Algorithm 1: the best achievable
-max-rank load ("all GPUs process the same amount of tokens" is the goal stated
-in Section 3.1) over every way of filling the spare slots with replicas.
+max-rank load (Section 3.1 states the goal: every GPU ends up with the same
+number of tokens) over every way of filling the spare slots with replicas.
 
 For a fixed placement the tokens of an expert may be split freely over the
 ranks that host it, so the smallest feasible max-rank load M is the smallest M

@@ -1,6 +1,6 @@
 """Oracle: rows that cross expert-parallel ranks (test infrastructure, CPU only).
 
-Background, "Routing incurs inter-device communication": after the scatter a
+Background, paragraph on the communication cost of routing: after the scatter a
 rank holds a share of the tokens regardless of where their experts are, so with
 N ranks and a balanced distribution a fraction (N-1)/N of every rank's rows
 leaves it, and the rank of the most popular expert receives skewness times the

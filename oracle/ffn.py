@@ -1,8 +1,8 @@
 """Oracle: grouped expert FFN, SwiGLU and ReLU forms (test infrastructure, CPU only).
 
-The expert FFN is the Mixtral-style SwiGLU block the paper models (Section 3.4,
-"SwiGLU activation"; Background, "FFN computation ... is increased by a factor of
-the skewness").  For a row x served by expert e:
+The expert FFN is the Mixtral-style SwiGLU block the paper models (Section 3.4
+lists SwiGLU among the Mixtral features it models; Background: the FFN time of the
+bottleneck GPU grows with the skewness).  For a row x served by expert e:
     g = x W1_e,  u = x W3_e,  h = g / (1 + exp(-g)) * u,  y = h W2_e
 with no biases.  Everything is fp64 on the exact input values and nothing is
 rounded in between.  The matrix products are numpy's fp64 matmul (a library

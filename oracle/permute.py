@@ -2,7 +2,7 @@
 (test infrastructure, CPU only).
 
 This stands where the all-to-all dispatch of expert parallelism is (Background,
-"Routing incurs inter-device communication") and realises the dispatch d of
+paragraph on the communication cost of routing) and realises the dispatch d of
 Algorithm 1 for a given plan.  An *assignment* is a = t*k + j: token t's j-th
 selected expert.  A *segment* is one slot (g, s) of the plan, global id g*S + s;
 the rows of a segment are the assignments that slot serves.

@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_plan_duplicates", "moe_permute_workspace_bytes", "moe_permute", "moe_permute_static",
     "moe_packed_weights_bytes",
     "moe_pack_weights", "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gather",
-    "moe_grouped_ffn_time_next_call",
+    "moe_grouped_ffn_fused", "moe_grouped_ffn_set_option", "moe_grouped_ffn_time_next_call",
     "moe_combine", "moe_comm_matrix", "moe_predictor_update", "moe_predictor_predict",
     "moe_packed_weights_relu_bytes", "moe_pack_weights_relu", "moe_grouped_ffn_relu",
 ]
@@ -88,6 +88,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_grouped_ffn_gather.restype = c_int
     lib.moe_grouped_ffn_gather.argtypes = [vp, c_int, c_int, c_int, vp, c_int, c_int, c_int, vp, vp, c_int, c_int,
                                            c_int, vp, vp, vp, c_sz, vp]
+    lib.moe_grouped_ffn_fused.restype = c_int
+    lib.moe_grouped_ffn_fused.argtypes = [vp, c_int, c_int, c_int, vp, vp, c_int, c_int, c_int, vp, vp, c_int, c_int,
+                                          c_int, vp, vp, vp, c_sz, vp]
+    lib.moe_grouped_ffn_set_option.restype = c_int
+    lib.moe_grouped_ffn_set_option.argtypes = [c_int, c_int]
     lib.moe_grouped_ffn_time_next_call.restype = c_int
     lib.moe_grouped_ffn_time_next_call.argtypes = [ctypes.POINTER(vp)]
     lib.moe_combine.restype = c_int
@@ -137,12 +142,18 @@ def dtype_code(t: torch.Tensor) -> int:
     raise MoeGpsError(f"unsupported dtype {t.dtype}")
 
 
-def moe_route_topk(logits: torch.Tensor, k: int):
+def moe_route_topk(logits: torch.Tensor, k: int, out=None):
+    """``out``: optional (topk_idx, topk_w) to write into."""
     lib = load_library()
     _need(logits, torch.float32, "logits")
     T, E = logits.shape
-    idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
-    w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    if out is None:
+        idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+        w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    else:
+        idx, w = out
+        _need(idx, torch.int32, "topk_idx")
+        _need(w, torch.float32, "topk_w")
     _check(lib.moe_route_topk(_ptr(logits), T, E, k, _ptr(idx), _ptr(w), _stream()), "moe_route_topk")
     return idx, w
 
@@ -155,15 +166,22 @@ def moe_histogram(idx: torch.Tensor, E: int, out: Optional[torch.Tensor] = None)
     return hist
 
 
-def moe_plan_duplicates(mode: int, hist_pred: torch.Tensor, G: int, S: int, c_max: int):
+def moe_plan_duplicates(mode: int, hist_pred: torch.Tensor, G: int, S: int, c_max: int, out=None):
+    """``out``: optional (slot_expert, slot_quota, rank_load_pred, n_iters) to write into."""
     lib = load_library()
     _need(hist_pred, torch.int32, "hist_pred")
     E = hist_pred.numel()
     dev = hist_pred.device
-    slot_expert = torch.empty(G * S, dtype=torch.int32, device=dev)
-    slot_quota = torch.empty(G * S, dtype=torch.int32, device=dev)
-    rank_load_pred = torch.empty(G, dtype=torch.int32, device=dev)
-    n_iters = torch.empty(1, dtype=torch.int32, device=dev)
+    if out is None:
+        slot_expert = torch.empty(G * S, dtype=torch.int32, device=dev)
+        slot_quota = torch.empty(G * S, dtype=torch.int32, device=dev)
+        rank_load_pred = torch.empty(G, dtype=torch.int32, device=dev)
+        n_iters = torch.empty(1, dtype=torch.int32, device=dev)
+    else:
+        slot_expert, slot_quota, rank_load_pred, n_iters = out
+        for name, t in (("slot_expert", slot_expert), ("slot_quota", slot_quota),
+                        ("rank_load_pred", rank_load_pred), ("n_iters", n_iters)):
+            _need(t, torch.int32, name)
     _check(lib.moe_plan_duplicates(mode, _ptr(hist_pred), E, G, S, c_max, _ptr(slot_expert), _ptr(slot_quota),
                                    _ptr(rank_load_pred), _ptr(n_iters), _stream()), "moe_plan_duplicates")
     return slot_expert, slot_quota, rank_load_pred, n_iters
@@ -287,8 +305,9 @@ def moe_grouped_ffn(x_perm: torch.Tensor, seg_offsets: torch.Tensor, slot_expert
 def moe_grouped_ffn_gather(x: torch.Tensor, assign_of_row: torch.Tensor, k: int, seg_offsets: torch.Tensor,
                            slot_expert: torch.Tensor, packed: torch.Tensor, E: int, ffn: int, seg_begin: int = 0,
                            seg_end: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
-                           out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """FFN with the row gather fused into the first product (no x_perm)."""
+                           out: Optional[torch.Tensor] = None, topk_w: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """FFN with the row gather fused into the first product (no x_perm).  With ``topk_w``
+    (moe_grouped_ffn_fused) the rows of the result are also multiplied by their gate weights."""
     lib = load_library()
     dt = dtype_code(x)
     if not x.is_contiguous() or not x.is_cuda:
@@ -305,18 +324,35 @@ def moe_grouped_ffn_gather(x: torch.Tensor, assign_of_row: torch.Tensor, k: int,
     need = moe_grouped_ffn_workspace_bytes(A, d, ffn, nseg, dt)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if topk_w is not None:
+        _need(topk_w, torch.float32, "topk_w")
+        _check(lib.moe_grouped_ffn_fused(_ptr(x), dt, T, k, _ptr(assign_of_row), _ptr(topk_w), d, ffn, E,
+                                         _ptr(seg_offsets), _ptr(slot_expert), nseg, seg_begin, seg_end, _ptr(packed),
+                                         _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
+               "moe_grouped_ffn_fused")
+        return y
     _check(lib.moe_grouped_ffn_gather(_ptr(x), dt, T, k, _ptr(assign_of_row), d, ffn, E, _ptr(seg_offsets),
                                       _ptr(slot_expert), nseg, seg_begin, seg_end, _ptr(packed), _ptr(y),
                                       _ptr(workspace), workspace.numel(), _stream()), "moe_grouped_ffn_gather")
     return y
 
 
-def moe_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_w: torch.Tensor, T: int, k: int,
+FFN_OPT_TILE1, FFN_OPT_TILE2, FFN_OPT_SPLIT_K, FFN_OPT_GROUP_N = 0, 1, 2, 3
+
+
+def moe_grouped_ffn_set_option(option: int, value: int) -> None:
+    """Process-wide override of an automatic choice inside the grouped FFN (tests, experiments)."""
+    _check(load_library().moe_grouped_ffn_set_option(option, value), "moe_grouped_ffn_set_option")
+
+
+def moe_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_w: Optional[torch.Tensor], T: int, k: int,
                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """``topk_w=None``: the rows already carry their gate weights and are only added."""
     lib = load_library()
     dt = dtype_code(y_perm)
     _need(row_of_assign, torch.int32, "row_of_assign")
-    _need(topk_w, torch.float32, "topk_w")
+    if topk_w is not None:
+        _need(topk_w, torch.float32, "topk_w")
     d = y_perm.shape[1]
     if out is None:
         out = torch.empty((T, d), dtype=y_perm.dtype, device=y_perm.device)

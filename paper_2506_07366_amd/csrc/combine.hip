@@ -1,6 +1,6 @@
 // Weighted un-permute: out[t] = sum_j w[t, j] * y_perm[row_of_assign[t*k + j]].
-// Stands where the all-to-all after the expert FFN is (Background: "The same
-// amount of communication happens for All-to-All shuffle after the FFN layers").
+// Stands where the all-to-all after the expert FFN is (Background, communication
+// paragraph: the return shuffle moves as many rows as the dispatch did).
 // One wavefront per token (for small batches several, each on its own slice of the
 // row); each lane owns 16-byte pieces of the row, gathers the k source rows,
 // accumulates in fp32 with j ascending and stores once.
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
 #pragma unroll
     for (int j = 0; j < MOE_MAX_TOPK; ++j) {
         rows[j] = j < k ? row_of_assign[(size_t)t * k + j] : 0;
-        w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
+        w[j] = j < k ? (topk_w ? topk_w[(size_t)t * k + j] : 1.0f) : 0.f;  // no weights: a plain sum (1 * v is exact)
     }
     const u32x4* src = (const u32x4*)y_perm;
     constexpr int N = BF16 ? 8 : 4;
@@ -100,7 +100,7 @@ extern "C" int moe_combine(const void* y_perm, int dtype, int T, int d, int k, c
     if (k > MOE_MAX_TOPK) return MOE_ERR_UNSUPPORTED;
     if (((size_t)d * dtype_size(dtype)) % 16 != 0) return MOE_ERR_UNSUPPORTED;
     if (T == 0) return MOE_OK;
-    if (!y_perm || !row_of_assign || !topk_w || !out) return MOE_ERR_INVALID_ARG;
+    if (!y_perm || !row_of_assign || !out) return MOE_ERR_INVALID_ARG;  // topk_w may be NULL: unweighted sum
     const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
     hipStream_t st = (hipStream_t)stream;
     // pieces per lane and step: enough 16-byte reads in flight (k * pieces) without running

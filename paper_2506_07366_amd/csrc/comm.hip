@@ -1,5 +1,5 @@
-// Rows that cross the emulated expert-parallel ranks (Background, "Routing incurs
-// inter-device communication": after the scatter a rank holds a share of the tokens
+// Rows that cross the emulated expert-parallel ranks (Background, paragraph on the
+// communication cost of routing: after the scatter a rank holds a share of the tokens
 // wherever their experts are, and the all-to-all after the FFN moves the same rows
 // back; Section 3.2.2: with Token-to-Expert prediction a correctly predicted token
 // is already on the rank of its expert).  Token t is owned by rank floor(t*G/T).

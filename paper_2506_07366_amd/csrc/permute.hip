@@ -1,7 +1,7 @@
 // Dispatch of assignments to replica segments and the token permutation: the
 // dispatch d of Algorithm 1 for a given plan, standing where the all-to-all
-// before the expert FFN is (Background, "Routing incurs inter-device
-// communication").
+// before the expert FFN is (Background, paragraph on the communication cost of
+// routing).
 //
 // Everything is a deterministic stable counting sort, built from one primitive:
 // the stable rank of an element among equal keys.  A workgroup owns a contiguous

@@ -29,10 +29,14 @@ def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
 
 
 class MoELayer:
-    def __init__(self, cfg: MoEConfig, device="cuda", fused_gather: bool = False):
+    def __init__(self, cfg: MoEConfig, device="cuda", fused_gather: bool = False, fused_weights: bool = False):
         """fused_gather: gather the token rows inside the first FFN product
-        (moe_grouped_ffn_gather) instead of materialising x_perm in moe_permute."""
+        (moe_grouped_ffn_gather) instead of materialising x_perm in moe_permute.
+        fused_weights (implies fused_gather): the second product also applies the gate weights
+        (moe_grouped_ffn_fused) and moe_combine only adds the k rows of a token."""
         self.cfg = cfg
+        self.fused_weights = fused_weights
+        fused_gather = fused_gather or fused_weights
         self.fused_gather = fused_gather
         self.dev = torch.device(device)
         c = cfg
@@ -73,16 +77,12 @@ class MoELayer:
 
     # individual steps (each is exactly one C-ABI call) ---------------------
     def route(self, logits):
-        lib = B.load_library()
-        c = self.cfg
-        B._check(lib.moe_route_topk(B._ptr(logits), c.T, c.E, c.k, B._ptr(self.topk_idx), B._ptr(self.topk_w),
-                                    B._stream()), "moe_route_topk")
+        B.moe_route_topk(logits, self.cfg.k, out=(self.topk_idx, self.topk_w))
 
     def histogram(self):
         B.moe_histogram(self.topk_idx, self.cfg.E, out=self.hist)
 
     def plan(self, mode, hist_pred: Optional[torch.Tensor], pred_idx: Optional[torch.Tensor]):
-        lib = B.load_library()
         c = self.cfg
         if mode == MODE_TOKEN:
             B.moe_histogram(pred_idx, c.E, out=self.hist_plan)
@@ -92,9 +92,8 @@ class MoELayer:
         else:
             hp = self.hist
         self._hp = hp
-        B._check(lib.moe_plan_duplicates(mode, B._ptr(hp), c.E, c.G, c.S, c.cmax, B._ptr(self.slot_expert),
-                                         B._ptr(self.slot_quota), B._ptr(self.rank_load_pred), B._ptr(self.n_iters),
-                                         B._stream()), "moe_plan_duplicates")
+        B.moe_plan_duplicates(mode, hp, c.G, c.S, c.cmax,
+                              out=(self.slot_expert, self.slot_quota, self.rank_load_pred, self.n_iters))
 
     def permute(self, mode, x, pred_idx):
         c = self.cfg
@@ -109,7 +108,8 @@ class MoELayer:
         if self.fused_gather:
             B.moe_grouped_ffn_gather(self._x, self.perm["assign_of_row"], c.k, self.perm["seg_offsets"],
                                      self.slot_expert, self.packed, c.E, c.ffn, seg_begin, seg_end,
-                                     workspace=self.ws_ffn, out=self.y_perm)
+                                     workspace=self.ws_ffn, out=self.y_perm,
+                                     topk_w=self.topk_w if self.fused_weights else None)
         else:
             B.moe_grouped_ffn(self.perm["x_perm"], self.perm["seg_offsets"], self.slot_expert, self.packed, c.E,
                               c.ffn, seg_begin, seg_end, workspace=self.ws_ffn, out=self.y_perm,
@@ -117,7 +117,8 @@ class MoELayer:
 
     def combine(self):
         c = self.cfg
-        B.moe_combine(self.y_perm, self.perm["row_of_assign"], self.topk_w, c.T, c.k, out=self.out)
+        B.moe_combine(self.y_perm, self.perm["row_of_assign"], None if self.fused_weights else self.topk_w, c.T, c.k,
+                      out=self.out)
 
     # the whole path -----------------------------------------------------------
     def step(self, logits: torch.Tensor, x: torch.Tensor, hist_pred: Optional[torch.Tensor] = None,

@@ -65,28 +65,33 @@ def test_missing_library_fails_loudly(tmp_path):
         binding.load_library(str(tmp_path / "nope.so"))
 
 
-def test_ffn_workspace_size_rule(monkeypatch):
-    """Host logic of the FFN workspace: the fp32 slabs of the split ragged tiles are part of it
-    exactly when the rule says so (bf16, few tiles per workgroup, slabs no larger than the
-    hidden activations), and the environment switch turns them off and on."""
+def test_ffn_workspace_size_rule():
+    """Host logic of the FFN workspace: the fp32 slabs of the split tiles are part of it
+    exactly when the rule says so (bf16, at most eight rounds of tiles per workgroup, segments
+    that are not slivers, at least 16 k-tiles), and the option turns them off and on."""
     from paper_2506_07366_amd import binding
     lib = binding.load_library()
     ws = lib.moe_grouped_ffn_workspace_bytes
-    h_mixtral = 8192 * 14336 * 2
-    slabs = 2 * 16 * 256 * 4096 * 4
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "0")
-    base = ws(8192, 4096, 14336, 16, 1)
-    assert h_mixtral <= base < h_mixtral + (1 << 20)
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "1")
-    assert ws(8192, 4096, 14336, 16, 1) - base >= slabs           # Mixtral-shaped batch: 640 tiles, split
-    assert ws(8192, 4096, 14336, 16, 0) == ws(8192, 4096, 14336, 16, 0)
-    big_off = ws(262144, 4096, 1536, 160, 1)
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "0")
-    assert ws(262144, 4096, 1536, 160, 1) == big_off              # many tiles per workgroup: never split
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "1")
-    f32_on = ws(8192, 4096, 14336, 16, 0)
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "0")
-    assert ws(8192, 4096, 14336, 16, 0) == f32_on                 # fp32 path: never split
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", "2")
-    assert ws(1024, 512, 1024, 12, 1) > ws(1024, 512, 64, 12, 1)  # forced, but not below 128 hidden columns
-    assert ws(-1, 64, 64, 1, 1) == 0 and ws(16, 64, 64, 0, 1) == 0
+    opt = lib.moe_grouped_ffn_set_option
+    SPLIT = binding.FFN_OPT_SPLIT_K
+    try:
+        h_mixtral = 8192 * 14336 * 2
+        assert opt(SPLIT, 0) == 0
+        base = ws(8192, 4096, 14336, 16, 1)
+        assert h_mixtral <= base < h_mixtral + (2 << 20)
+        assert opt(SPLIT, -1) == 0
+        # Mixtral-shaped batch: 2-3 rounds of tiles.  Room for 5/8 of a round of tiles in half-tile M-tiles (22), 4 parts each
+        assert ws(8192, 4096, 14336, 16, 1) - base >= 22 * 4 * 256 * 4096 * 4
+        big_auto = ws(262144, 4096, 1536, 160, 1)
+        dec_auto = ws(1024, 4096, 1536, 160, 1)
+        f32_auto = ws(8192, 4096, 14336, 16, 0)
+        assert opt(SPLIT, 0) == 0
+        assert ws(262144, 4096, 1536, 160, 1) == big_auto             # many rounds per workgroup: never split
+        assert ws(1024, 4096, 1536, 160, 1) == dec_auto               # a few rows per segment: never split
+        assert ws(8192, 4096, 14336, 16, 0) == f32_auto               # fp32 path: never split
+        assert opt(SPLIT, 1) == 0
+        assert ws(1024, 512, 1024, 12, 1) > ws(1024, 512, 64, 12, 1)  # forced, but not with a single k-tile
+        assert ws(-1, 64, 64, 1, 1) == 0 and ws(16, 64, 64, 0, 1) == 0
+        assert opt(SPLIT, 2) == -1 and opt(99, 0) == -1 and opt(binding.FFN_OPT_TILE1, 2) == -1
+    finally:
+        opt(SPLIT, -1)

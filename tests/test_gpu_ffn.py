@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from oracle import grouped_ffn, ffn_rows, combine, moe_layer
+from oracle.histogram import skewness
 from oracle.ffn import ffn_rows_relu
 from paper_2506_07366_amd import binding as B
 from paper_2506_07366_amd import workloads as wl
@@ -16,6 +17,28 @@ from gpu_util import Case, dev_i32, to_host_f32, weights_storage, shape_key
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture
+def ffn_options():
+    """Sets overrides of the grouped FFN's automatic choices and restores the defaults afterwards."""
+    def set_(tile1=-1, tile2=-1, split=-1, group_n=0):
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE1, tile1)
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE2, tile2)
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_SPLIT_K, split)
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_GROUP_N, group_n)
+    yield set_
+    set_()
+
+
+def expert_row_lists(seg_offsets, slot_expert, E):
+    """Rows of x_perm per expert in the order the FFN tiles them: segments of the expert in
+    ascending slot id, rows ascending."""
+    lists = [[] for _ in range(E)]
+    for s_, e in enumerate(slot_expert):
+        if 0 <= e < E:
+            lists[e].extend(range(int(seg_offsets[s_]), int(seg_offsets[s_ + 1])))
+    return lists
 
 
 def host_weights(cfg):
@@ -102,18 +125,24 @@ def test_layer_full_compare(name, mode):
     rep = layer.load_report()
     assert rep["makespan"] == int(ref["perm"]["rank_load"].max())
     assert rep["n_iters"] == ref["plan"].n_iters
+    assert rep["skewness"] == pytest.approx(skewness(ref["hist"] if "hist" in ref else case.hist), rel=1e-12)
+    assert rep["imbalance"] == pytest.approx(float(ref["perm"]["rank_load"].max()) * cfg.G / cfg.A, rel=1e-12)
 
 
-FULL = ["cfg2_mixtral_dist", "cfg3_mixtral_t2e", "cfg4_finegrained", "cfg5_prefill_a1_m1", "cfg5_prefill_a0.1_m2",
-        "cfg5_prefill_a10_m0", "cfg5_decode_m1", "cfg5_decode_m0", "cfg5_decode_m2", "cfg6_switch_relu", "cfg7_llama_moe"]
+FULL = ["cfg2_mixtral_dist", "cfg3_mixtral_t2e", "cfg4_finegrained"] + \
+       [f"cfg5_prefill_a{a}_m{m}" for a in ("0.1", "1", "10") for m in (0, 1, 2)] + \
+       ["cfg5_decode_m0", "cfg5_decode_m1", "cfg5_decode_m2", "cfg6_switch_relu", "cfg7_llama_moe"]
 
 
 @pytest.mark.parametrize("name", FULL)
 def test_layer_full_size_sampled(name):
     """Full-size configs in the launch configuration the benchmark times: integer
     outputs compared in full, FFN / layer outputs on sampled rows the oracle can
-    compute one by one (all k rows of sampled tokens, the first and last row of
-    every non-empty segment, rows either side of every 64-row tile boundary)."""
+    compute one by one: all k rows of sampled tokens, the first and last row of
+    every non-empty segment, and the rows either side of every tile boundary the
+    kernels can use (rows are tiled per expert, over all its segments, in tiles of
+    256 or 128 rows: every multiple of 128 in every expert's row list).  The load
+    report is compared with the oracle's skewness and rank loads."""
     cfg = wl.CONFIGS[name]
     case = Case(cfg)
     Ws = host_weights(cfg)
@@ -139,9 +168,9 @@ def test_layer_full_size_sampled(name):
         lo, hi = int(so[s]), int(so[s + 1])
         if hi > lo:
             rows.update([lo, hi - 1])
-            for b in range(lo + 64, hi, 64):      # tile boundaries inside the segment
-                if rng.random() < 0.25:
-                    rows.update([b - 1, b])
+    for lst in expert_row_lists(so, case.plan.slot_expert, cfg.E):
+        for b in range(128, len(lst), 128):       # every tile boundary inside the expert's rows
+            rows.update([lst[b - 1], lst[b]])
     rows = np.array(sorted(rows), dtype=np.int64)
     aor = case.perm["assign_of_row"]
     seg_of_row = np.searchsorted(so, rows, side="right") - 1
@@ -170,6 +199,12 @@ def test_layer_full_size_sampled(name):
     # properties that hold at any size
     assert int(layer.perm["rank_load"].sum()) == cfg.A
     assert torch.isfinite(out.float()).all()
+    # load report against the oracle: skewness of the histogram, bottleneck rank over the mean
+    rep = layer.load_report()
+    assert rep["skewness"] == pytest.approx(skewness(case.hist), rel=1e-12)
+    assert rep["imbalance"] == pytest.approx(float(case.perm["rank_load"].max()) * cfg.G / cfg.A, rel=1e-12)
+    assert rep["makespan"] == int(case.perm["rank_load"].max())
+    assert rep["rank_load"] == case.perm["rank_load"].tolist()
 
 
 def test_output_independent_of_plan_mode():
@@ -310,29 +345,29 @@ def test_ffn_one_huge_segment_and_empty_rest():
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
 
 
-@pytest.mark.parametrize("split", [0, 2])
-@pytest.mark.parametrize("variant", range(11))
-def test_ffn_every_tile_variant(variant, split, monkeypatch):
-    """The tile shapes and K-loop schedules built into the library (chosen by environment
-    variable; index 3 is the default) all compute the same FFN, with the ragged tiles of the
-    second product computed whole (0) or as two halves of K added up afterwards (2: forced;
-    320 hidden columns are 5 or 10 k-tiles, so the halves are unequal for the 64-wide ones)."""
-    monkeypatch.setenv("MOEGPS_FFN_TILE1", str(variant))
-    monkeypatch.setenv("MOEGPS_FFN_TILE2", str(variant))
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
+@pytest.mark.parametrize("split", [0, 1])
+@pytest.mark.parametrize("tile2", [0, 1])
+@pytest.mark.parametrize("tile1", [0, 1])
+def test_ffn_every_tile_variant(tile1, tile2, split, ffn_options):
+    """The tile shapes built into the library (forced through moe_grouped_ffn_set_option) all
+    compute the same FFN, with the closing tiles of the second product computed whole (0) or as
+    parts of K added up afterwards (1: forced; 320 hidden columns are 5 k-tiles, so the four
+    parts are unequal)."""
+    ffn_options(tile1=tile1, tile2=tile2, split=split)
     cfg = wl.MoEConfig("v", T=1, d=256, ffn=320, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
     seg_sizes = [1, 0, 127, 129, 0, 256, 257, 63, 300, 0, 5, 64]
     slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 0]
-    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=variant)
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=tile1 * 2 + tile2)
     scale = np.max(np.abs(ref))
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
 
 
 @pytest.mark.parametrize("relu", [False, True])
-def test_ffn_split_tails_matches_whole_tiles(relu, monkeypatch):
-    """Ragged tiles computed as two halves of K: same result as whole tiles up to the fp32
-    association of the two partial sums (one bf16 rounding step of the output), rows of
-    full-height tiles bit-identical, and rows outside the slot range untouched."""
+def test_ffn_split_k_matches_whole_tiles(relu, ffn_options):
+    """Closing tiles computed as parts of K: same result as whole tiles up to the fp32
+    association of the partial sums (one bf16 rounding step of the output), rows outside the
+    slot range untouched, and the same answer on a second run (the order in which workgroups
+    claim tiles does not reach the result)."""
     cfg = wl.MoEConfig("s", T=1, d=192, ffn=688, E=4, k=1, G=4, S=3, dtype="bf16", mode=0, seed=29)
     rng = np.random.default_rng(31)
     seg_sizes = [300, 0, 256, 1, 513, 0, 77, 255, 128, 0, 31, 640]
@@ -347,32 +382,118 @@ def test_ffn_split_tails_matches_whole_tiles(relu, monkeypatch):
         packed = B.moe_pack_weights(*dev_weights(cfg, (W1s, W3s, W2s)))
     xd = to_device(wl.to_storage(x, "bf16"), "bf16")
     out = {}
-    for split in (0, 2):
-        monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
+    for split in (0, 1):
+        ffn_options(split=split)
         out[split] = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn,
                                                    relu=relu))
+        again = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn,
+                                              relu=relu))
+        assert np.array_equal(out[split], again)
         out[split, "range"] = to_host_f32(B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E,
                                                             cfg.ffn, seg_begin=3, seg_end=8, relu=relu))
     Wf = [wl.from_storage(w, "bf16") for w in (W1s, W3s, W2s)]
     ref = grouped_ffn(x, so, slot_expert, Wf[0], None if relu else Wf[1], Wf[2])
     scale = np.max(np.abs(ref))
-    for split in (0, 2):
+    for split in (0, 1):
         assert np.all(np.max(np.abs(out[split] - ref), axis=1) <= TOL["bf16"] * scale)
         r = out[split, "range"]
-        assert np.array_equal(r[so[3]:so[8]], out[split][so[3]:so[8]])
+        assert np.max(np.abs(r[so[3]:so[8]] - ref[so[3]:so[8]])) <= TOL["bf16"] * scale
         assert np.all(r[:so[3]] == 0) and np.all(r[so[8]:] == 0)
-    # the default tile height here is 128 (few tiles): rows below the last multiple of 128 of a segment are whole tiles
+    # whole (unsplit) tiles accumulate a row's products in the same order whatever else is launched
+    # with them: the slot range alone gives the same bits as the full launch
+    assert np.array_equal(out[0, "range"][so[3]:so[8]], out[0][so[3]:so[8]])
+    assert np.max(np.abs(out[0] - out[1])) <= 2.0 ** -7 * scale
+
+
+def test_ffn_replicas_of_one_expert_share_tiles():
+    """Several segments of the range host the same expert (replicas hold the same weights):
+    their rows are tiled together, whatever their sizes, and every row still gets its own
+    expert's result; a row's result does not depend on which replica served it."""
+    cfg = wl.MoEConfig("r", T=1, d=128, ffn=256, E=4, k=1, G=6, S=2, dtype="bf16", mode=0, seed=37)
+    seg_sizes = [3, 200, 0, 58, 130, 1, 256, 7, 0, 90, 511, 2]
+    slot_expert = [0, 1, 0, 0, 2, 0, 1, 0, -1, 3, 0, 1]      # expert 0 in seven slots, one of them empty
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=12)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
+    # the same rows with every segment on its own (one launch per slot): same values up to the
+    # position of the rows inside their tiles, which does not change a row's sum
+    rng = np.random.default_rng(12)
+    x = wl.quantize(rng.standard_normal((int(sum(seg_sizes)), cfg.d)).astype(np.float32), "bf16")
+    Ws = host_weights(cfg)
+    packed = B.moe_pack_weights(*dev_weights(cfg, Ws))
+    xd = to_device(wl.to_storage(x, "bf16"), "bf16")
+    y = torch.zeros_like(xd)
     for s_ in range(len(seg_sizes)):
-        full = so[s_] + (seg_sizes[s_] // 128) * 128
-        assert np.array_equal(out[0][so[s_]:full], out[2][so[s_]:full])
-    assert np.max(np.abs(out[0] - out[2])) <= 2.0 ** -7 * scale
+        B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn, seg_begin=s_, seg_end=s_ + 1,
+                          out=y)
+    assert np.array_equal(to_host_f32(y), got)
 
 
-@pytest.mark.parametrize("split", [0, 2])
-def test_ffn_workspace_exact_size_accepted_one_byte_less_refused(split, monkeypatch):
+@pytest.mark.parametrize("name,mode", [("cfg1_tiny_f32", 1), ("mid_bf16", 0), ("mid_bf16", 1), ("mid_bf16", 2)])
+def test_fused_gate_weights_against_oracle(name, mode):
+    """Gate weights applied by the second product (moe_grouped_ffn_fused) and a plain sum in
+    moe_combine: the layer output against the oracle's combine of the oracle's FFN, and the
+    weighted rows against w * (oracle row).  Rule for the bits: fp32 rows are exactly
+    fl(w * y) of the unweighted path's y; bf16 rows are rounded once from w * (fp32 sum), so
+    they differ from bf16(w * bf16(y)) by at most one rounding step."""
+    cfg = wl.CONFIGS[name].replace(mode=mode, acc=0.9)
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    Wf = [wl.from_storage(w, cfg.dtype) for w in Ws]
+    ref = moe_layer(mode, case.logits, case.x, *Wf, cfg.k, cfg.G, cfg.S, cfg.cmax,
+                    hist_pred=case.hist_plan, pred_idx=case.pred_idx)
+    dw = dev_weights(cfg, Ws)
+    plain = MoELayer(cfg, fused_gather=True)
+    plain.set_weights(*dw)
+    plain.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+    fused = MoELayer(cfg, fused_weights=True)
+    fused.set_weights(*dw)
+    out = fused.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+    torch.cuda.synchronize()
+    assert rel_err(to_host_f32(out), ref["out"]) <= TOL[cfg.dtype]
+    w_row = case.w.reshape(-1)[ref["perm"]["assign_of_row"]]                 # gate weight of every row
+    yw_ref = ref["y_perm"] * w_row[:, None]
+    yw = to_host_f32(fused.y_perm)
+    assert np.max(np.abs(yw - yw_ref)) <= TOL[cfg.dtype] * np.max(np.abs(ref["y_perm"]))
+    y_plain = to_host_f32(plain.y_perm)
+    w32 = fused.topk_w.cpu().numpy().reshape(-1)[ref["perm"]["assign_of_row"]].astype(np.float32)
+    if cfg.dtype == "f32":
+        assert np.array_equal(yw, y_plain * w32[:, None])
+    else:
+        twice = wl.quantize(y_plain * w32[:, None], "bf16")                  # rounded twice: bf16(w * bf16(sum))
+        step = np.maximum(np.abs(yw), np.abs(twice)) * 2.0 ** -7             # a bf16 rounding step at that size
+        assert np.all(np.abs(yw - twice) <= 2 * step + 1e-30)
+
+
+def test_fused_gate_weights_full_size_sampled():
+    """The fused path (row gather in the first product, gate weights in the second, plain sum
+    in the combine) at the headline size: layer output of sampled tokens against the oracle."""
+    cfg = wl.CONFIGS["cfg2_mixtral_dist"]
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    layer = MoELayer(cfg, fused_weights=True)
+    layer.set_weights(*dev_weights(cfg, Ws))
+    out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.perm["row_of_assign"].cpu().numpy(), case.perm["row_of_assign"])
+    rng = np.random.default_rng(77)
+    toks = np.sort(rng.choice(cfg.T, size=96, replace=False))
+    out_ref = np.zeros((toks.size, cfg.d))
+    for i, t in enumerate(toks):
+        for j in range(cfg.k):
+            e = int(case.idx[t, j])
+            y = ffn_rows(case.x[t:t + 1], wl.from_storage(Ws[0][e], cfg.dtype), wl.from_storage(Ws[1][e], cfg.dtype),
+                         wl.from_storage(Ws[2][e], cfg.dtype))
+            out_ref[i] += case.w[t, j] * y[0]
+    out_got = to_host_f32(out[torch.from_numpy(toks).cuda()])
+    assert np.max(np.abs(out_got - out_ref)) <= TOL["bf16"] * np.max(np.abs(out_ref))
+
+
+@pytest.mark.parametrize("split", [-1, 1])
+def test_ffn_workspace_exact_size_accepted_one_byte_less_refused(split, ffn_options):
     """The size moe_grouped_ffn_workspace_bytes reports is what the call needs: a caller-owned
     workspace of exactly that size works, one byte less is refused before anything is launched."""
-    monkeypatch.setenv("MOEGPS_FFN_SPLIT_TAILS", str(split))
+    ffn_options(split=split)
     cfg = wl.MoEConfig("w", T=1, d=128, ffn=256, E=3, k=1, G=2, S=2, dtype="bf16", mode=0, seed=33)
     rng = np.random.default_rng(34)
     seg_sizes = [70, 300, 0, 129]

@@ -87,7 +87,7 @@ def test_balanced_within_one_with_ample_slots():
 
 def test_constraints_respected_and_never_worse_than_home():
     rng = np.random.default_rng(11)
-    for trial in range(60):
+    for trial in range(80):
         E = int(rng.integers(2, 13))
         G = int(rng.integers(2, 7))
         H = -(-E // G)
@@ -105,16 +105,23 @@ def test_constraints_respected_and_never_worse_than_home():
 
 def test_count_based_equals_literal_per_token_algorithm():
     rng = np.random.default_rng(2)
-    checked = 0
-    for trial in range(60):
+    ties = 0
+    for trial in range(80):
         E = int(rng.integers(2, 7))
         G = int(rng.integers(2, 5))
         H = -(-E // G)
         S = H + int(rng.integers(0, 3))
         c_max = int(rng.integers(1, G + 1))
-        T = int(rng.integers(5, 90))
-        p = rng.dirichlet(np.full(E, 0.4))
-        f = rng.choice(E, size=T, p=p)
+        if trial % 2 == 0:
+            T = int(rng.integers(5, 90))
+            p = rng.dirichlet(np.full(E, 0.4))
+            f = rng.choice(E, size=T, p=p)
+        else:
+            # counts from a small set of powers of two: halving the gaps keeps producing
+            # experts with equal counts on one rank, home experts and copies alike
+            f = rng.permutation(np.repeat(np.arange(E), rng.choice([0, 4, 8, 16, 32], size=E)))
+            if f.size == 0:
+                f = np.zeros(3, dtype=np.int64)
         n = np.bincount(f, minlength=E)
         plan = plan_duplicates(1, n, E, G, S, c_max)
         load, P, d, it = alg1_literal(f, E, G, S, c_max)
@@ -125,33 +132,59 @@ def test_count_based_equals_literal_per_token_algorithm():
             for s in range(S):
                 if se[g, s] >= 0:
                     mine[se[g, s], g] += q[g, s]
-        # equal-count experts on the hot rank can be taken in a different order by
-        # the two forms (slot order vs expert id); only tie-free runs are compared
-        if not _has_expert_tie(f, E, G, S, c_max):
-            assert np.array_equal(mine, load), (E, G, S, c_max, n)
-            assert plan.n_iters == it
-            checked += 1
-    assert checked >= 25
+        # every run is compared, ties included: equal-count experts on the hot rank are
+        # taken in slot order by both forms
+        assert np.array_equal(mine, load), (E, G, S, c_max, n)
+        assert plan.n_iters == it
+        assert P == {(int(se[g, s]), g) for g in range(G) for s in range(S) if se[g, s] >= 0}
+        ties += _has_expert_tie(f, E, G, S, c_max)
+    assert ties >= 5      # the inputs do exercise the tie-break
+
+
+TIE_CASES = [  # (E, G, S, c_max, counts): runs in which taking tied experts by id instead of by slot changes the loads
+    (3, 3, 3, 3, [8, 3, 3]), (3, 3, 3, 3, [8, 4, 3]), (5, 3, 3, 3, [16, 8, 6, 0, 3]), (5, 3, 3, 2, [16, 4, 2, 6, 8]),
+    (5, 3, 4, 3, [1, 8, 8, 16, 8])]
+
+
+@pytest.mark.parametrize("E,G,S,c_max,n", TIE_CASES)
+def test_tied_experts_are_taken_in_slot_order(E, G, S, c_max, n):
+    """A copy with a low expert id sits in a higher slot than the rank's home expert; when
+    both serve equally many tokens on the hot rank the home expert (lower slot) goes first."""
+    f = np.repeat(np.arange(E), n)
+    plan = plan_duplicates(1, n, E, G, S, c_max)
+    load, P, d, it = alg1_literal(f, E, G, S, c_max)
+    se = plan.slot_expert.reshape(G, S)
+    q = plan.slot_quota.reshape(G, S)
+    mine = np.zeros((E, G), dtype=np.int64)
+    for g in range(G):
+        for s in range(S):
+            if se[g, s] >= 0:
+                mine[se[g, s], g] += q[g, s]
+    assert np.array_equal(mine, load) and plan.n_iters == it
+    if n == [8, 3, 3]:
+        # by hand: L = [8,3,3]; 3 tokens of e0 go to a new copy on rank 1 (slot 1) -> L = [5,6,3];
+        # rank 1 is hot with e1 (slot 0) and e0 (slot 1) at 3 tokens each: e1 goes first, 2 of
+        # its tokens move to a new copy on rank 2 -> L = [5,4,5], max - min = 1: done.  Taking e0
+        # in the tie would leave e1 without a copy.
+        assert (1, 2) in P and it == 2
+        assert load.tolist() == [[5, 3, 0], [0, 1, 2], [0, 0, 3]]
 
 
 def _has_expert_tie(f, E, G, S, c_max):
-    """Replay the literal algorithm and report whether two experts on the hot GPU
-    ever had equal positive token counts."""
-    load_hist = []
+    """Replay the literal algorithm iteration by iteration and report whether two experts
+    on the hot GPU ever served equally many tokens when one had to be chosen."""
     it = 0
-    while True:
+    while it <= 200:
         load, P, d, n_it = alg1_literal(f, E, G, S, c_max, max_iters=it)
         L = load.sum(axis=0)
-        g_h = int(np.argmax(L))
-        col = load[:, g_h]
+        col = load[:, int(np.argmax(L))]
         pos = col[col > 0]
-        if len(set(pos.tolist())) != len(pos):
+        if L.max() - L.min() > 1 and len(set(pos.tolist())) != len(pos):
             return True
         if n_it < it:
             return False
         it += 1
-        if it > 200:
-            return False
+    return False
 
 
 def _flow_feasible(n, hosts, G, M):
