@@ -1,7 +1,8 @@
 // Gate top-k: the token->expert map f of Algorithm 1 (Background: tokens are
 // routed to their top-K experts).  A group of LPT lanes of a 64-wide wavefront
 // owns one token; every lane keeps VPL logits in registers and the k winners are
-// found by k rounds of a cross-lane arg-max (DPP lane permutes inside a row of 16).  Order is (logit
+// found by k rounds of a cross-lane arg-max (DPP lane permutes inside a row of 16
+// lanes; a group is at most one such row up to 512 experts).  Order is (logit
 // descending, expert index ascending), so equal logits go to the lowest index.
 // Gate weights are a softmax over the k selected logits.
 #include "common.h"
@@ -46,28 +47,51 @@ __device__ __forceinline__ void group_best(float& v, int& e) {
     if constexpr (LPT == 64) shfl_level<32>(v, e);
 }
 
+// LPT lanes own one token; lane `sub` of the group keeps the VPL consecutive logits
+// [sub*VPL, (sub+1)*VPL) in registers, so a token's row is read as one contiguous run
+// (16-byte loads where the row layout allows).  With more than 16 experts a group is one
+// row of 16 lanes (four tokens per wavefront) and every cross-lane step stays inside the
+// vector ALU's lane permutes; only above 512 experts does a group span two rows.
+// Lane j of the group keeps winner j; the softmax is taken once at the end, one
+// exponential per lane, summed over the group's lanes.
 template <int LPT, int VPL>
 __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ logits, int T, int E,
                                                           int k, int32_t* __restrict__ topk_idx,
                                                           float* __restrict__ topk_w) {
+    static_assert(VPL <= 32, "one bit per logit of a lane");
     constexpr int TPW = kWave / LPT;  // tokens per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int sub = lane % LPT;
     const int token = wave * TPW + lane / LPT;
     const bool live = token < T;
-    const int tok = live ? token : (T - 1);  // keep every lane in the shuffles
+    const int tok = live ? token : (T - 1);  // keep every lane in the lane permutes
 
     const float NEG_INF = -__builtin_huge_valf();
     float v[VPL];
+    const float* row = logits + (size_t)tok * E;
+    const int e0 = sub * VPL;
+    if ((VPL % 4 == 0) && (E % 4 == 0)) {
+        // rows start on 16-byte boundaries and a lane's run is a whole number of 16-byte pieces
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) {
-        const int e = sub + i * LPT;
-        v[i] = (e < E) ? logits[(size_t)tok * E + e] : NEG_INF;
+        for (int i = 0; i < VPL; i += 4) {
+            if (e0 + i < E) {
+                const float4 q = *(const float4*)(row + e0 + i);
+                v[i] = q.x;
+                v[i + 1] = q.y;
+                v[i + 2] = q.z;
+                v[i + 3] = q.w;
+            } else {
+                v[i] = v[i + 1] = v[i + 2] = v[i + 3] = NEG_INF;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) v[i] = (e0 + i < E) ? row[e0 + i] : NEG_INF;
     }
 
     unsigned taken = 0;
-    float l0 = 0.f, sum = 0.f, my_ex = 0.f;
+    float l0 = 0.f, my_v = 0.f;
     int my_e = 0;
     for (int j = 0; j < k; ++j) {
         // best remaining candidate of this lane; padding columns carry their own
@@ -76,25 +100,31 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
         int be = 0x7fffffff;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
-            const int ce = sub + i * LPT;
+            const int ce = e0 + i;
             const bool take = !((taken >> i) & 1u) && better(v[i], ce, bv, be);
             bv = take ? v[i] : bv;
             be = take ? ce : be;
         }
         group_best<LPT>(bv, be);
         // the owner retires the winner
-        if ((be % LPT) == sub) taken |= 1u << (be / LPT);
+        if (be / VPL == sub) taken |= 1u << (be % VPL);
         if (j == 0) l0 = bv;
-        const float ex = expf(bv - l0);
-        sum += ex;
         if (sub == j) {
-            my_ex = ex;
+            my_v = bv;
             my_e = be;
         }
     }
+    const float ex = sub < k ? expf(my_v - l0) : 0.f;
+    float sum = ex;
+    if constexpr (LPT >= 2) sum += __shfl_xor(sum, 1, kWave);
+    if constexpr (LPT >= 4) sum += __shfl_xor(sum, 2, kWave);
+    if constexpr (LPT >= 8) sum += __shfl_xor(sum, 4, kWave);
+    if constexpr (LPT >= 16) sum += __shfl_xor(sum, 8, kWave);
+    if constexpr (LPT >= 32) sum += __shfl_xor(sum, 16, kWave);
+    if constexpr (LPT == 64) sum += __shfl_xor(sum, 32, kWave);
     if (live && sub < k) {
         topk_idx[(size_t)token * k + sub] = my_e;
-        topk_w[(size_t)token * k + sub] = my_ex / sum;
+        topk_w[(size_t)token * k + sub] = ex / sum;
     }
 }
 
@@ -117,16 +147,16 @@ extern "C" int moe_route_topk(const float* logits, int T, int E, int k, int32_t*
     if (T == 0) return MOE_OK;
     if (!logits || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    // lanes per token: the power of two covering E (at most a full wavefront);
-    // k <= min(E, 16) <= LPT always holds
+    // lanes per token: the power of two covering E up to one row of 16 lanes, which then
+    // holds ceil(E/16) logits per lane; k <= min(E, 16) <= lanes always holds
     if (E <= 2) return launch_route<2, 1>(logits, T, E, k, topk_idx, topk_w, st);
     if (E <= 4) return launch_route<4, 1>(logits, T, E, k, topk_idx, topk_w, st);
     if (E <= 8) return launch_route<8, 1>(logits, T, E, k, topk_idx, topk_w, st);
     if (E <= 16) return launch_route<16, 1>(logits, T, E, k, topk_idx, topk_w, st);
-    if (E <= 32) return launch_route<32, 1>(logits, T, E, k, topk_idx, topk_w, st);
-    if (E <= 64) return launch_route<64, 1>(logits, T, E, k, topk_idx, topk_w, st);
-    if (E <= 128) return launch_route<64, 2>(logits, T, E, k, topk_idx, topk_w, st);
-    if (E <= 256) return launch_route<64, 4>(logits, T, E, k, topk_idx, topk_w, st);
-    if (E <= 512) return launch_route<64, 8>(logits, T, E, k, topk_idx, topk_w, st);
-    return launch_route<64, 16>(logits, T, E, k, topk_idx, topk_w, st);
+    if (E <= 32) return launch_route<16, 2>(logits, T, E, k, topk_idx, topk_w, st);
+    if (E <= 64) return launch_route<16, 4>(logits, T, E, k, topk_idx, topk_w, st);
+    if (E <= 128) return launch_route<16, 8>(logits, T, E, k, topk_idx, topk_w, st);
+    if (E <= 256) return launch_route<16, 16>(logits, T, E, k, topk_idx, topk_w, st);
+    if (E <= 512) return launch_route<16, 32>(logits, T, E, k, topk_idx, topk_w, st);
+    return launch_route<32, 32>(logits, T, E, k, topk_idx, topk_w, st);
 }

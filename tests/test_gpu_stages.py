@@ -20,7 +20,8 @@ INT_CFGS = ["cfg1_tiny_f32", "cfg2_mixtral_dist", "cfg3_mixtral_t2e", "cfg4_fine
 # ---------------------------------------------------------------- routing
 @pytest.mark.parametrize("E,k,T", [(8, 2, 1000), (64, 6, 777), (128, 8, 513), (5, 5, 100), (7, 1, 64), (1, 1, 10),
                                    (2, 2, 33), (16, 4, 129), (33, 3, 65), (200, 16, 70), (1024, 8, 40),
-                                   (300, 5, 1)])
+                                   (300, 5, 1), (48, 3, 100), (34, 2, 50), (96, 6, 333), (256, 8, 100),
+                                   (512, 16, 30), (513, 7, 20), (17, 16, 70), (128, 16, 4099)])
 def test_route_random(E, k, T):
     rng = np.random.default_rng(E * 1000 + k)
     logits = rng.standard_normal((T, E)).astype(np.float32)
@@ -32,7 +33,7 @@ def test_route_random(E, k, T):
 
 def test_route_ties_lowest_index():
     rng = np.random.default_rng(1)
-    for E, k in [(16, 4), (128, 8), (8, 2)]:
+    for E, k in [(16, 4), (128, 8), (8, 2), (64, 6), (40, 5), (512, 16), (1000, 9)]:
         logits = (np.round(rng.standard_normal((500, E)) * 2) / 4).astype(np.float32)
         logits[0, :] = 0.0                      # an all-equal row
         idx, w = B.moe_route_topk(torch.from_numpy(logits).cuda(), k)
