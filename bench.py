@@ -29,25 +29,27 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # Bytes moved between the L2s and memory by one launch of the gate/up product, from hardware
 # counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter
-# reads for the library's plain copy kernel; summary under profiles/).  The figures belong to
-# one version of the kernel source: they are reported only while its digest still matches.
+# reads for the library's plain copy kernel).  The figures come from the profile named in
+# `profile`, not from this run, and belong to one version of the kernel source: they are
+# reported only while its digest still matches and no tuning option is forced.
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "70608326d57ee485c1d04115da891052ca0da34c1b8fe32a43d0fd21fbbc1928",
-                          "fetch_bytes": 5992784827, "write_bytes": 250819485},
+    "cfg2_mixtral_dist": {"source_sha256": "", "fetch_bytes": 0, "write_bytes": 0,
+                          "profile": "profiles/gemm1_cfg2_mixtral_traffic_counters.md"},
 }
 
 
 def measured_traffic(config_name):
+    """(bytes per launch, profile it comes from) or (None, None)."""
     import hashlib
     rec = TRAFFIC.get(config_name)
     if not rec or not rec["source_sha256"] or not os.path.exists(KERNEL_SOURCE):
-        return None
+        return None, None
     with open(KERNEL_SOURCE, "rb") as f:
         if hashlib.sha256(f.read()).hexdigest() != rec["source_sha256"]:
-            return None
-    return rec["fetch_bytes"] + rec["write_bytes"]
+            return None, None
+    return rec["fetch_bytes"] + rec["write_bytes"], rec["profile"]
 
 
 def describe(cfg):
@@ -253,6 +255,7 @@ def main():
 
     flops1 = (2.0 if cfg.act == "relu" else 4.0) * cfg.A * cfg.d * cfg.ffn   # gate + up products (ReLU form: one)
     flops2 = 2.0 * cfg.A * cfg.d * cfg.ffn      # down product
+    traffic, traffic_source = measured_traffic(args.config)
     if bf16:
         g1_ms = float(np.mean([q[0].elapsed_time(q[1]) for q in evs]))
         g2_ms = float(np.mean([q[2].elapsed_time(q[3]) for q in evs]))
@@ -260,10 +263,28 @@ def main():
         roofline = {"bound": "mfma", "kernel": ("grouped_gemm_bf16_kernel<relu> (first product)" if cfg.act == "relu"
                                                 else "grouped_gemm_bf16_kernel<swiglu> (gate/up product)"),
                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config), "avg_ms": g1_ms,
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
+                    "avg_ms": g1_ms,
                     "down_product": {"avg_ms": g2_ms, "achieved": flops2 / (g2_ms * 1e-3) / 1e12,
                                      "frac": flops2 / (g2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
                     "ffn_frac_of_peak": (flops1 + flops2) / ((g1_ms + g2_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        # A batch of a few rows per segment (decode) streams weights: the ceiling of its FFN is
+        # HBM bandwidth, and the bytes are those of the experts that got at least one row (each
+        # expert's three matrices are read once, however many replicas serve it), plus the rows
+        # in and out and the hidden activations written and read.
+        if cfg.A < 64 * cfg.nseg:
+            so = layer.perm["seg_offsets"].cpu().numpy()
+            se = layer.slot_expert.cpu().numpy()
+            touched = sorted({int(e) for s_, e in enumerate(se) if e >= 0 and so[s_ + 1] > so[s_]})
+            n_mat = 2 if cfg.act == "relu" else 3
+            bytes_ffn = (n_mat * cfg.d * cfg.ffn * 2 * len(touched) + 2 * cfg.A * cfg.d * 2
+                         + 2 * cfg.A * cfg.ffn * 2)
+            ach = bytes_ffn / ((g1_ms + g2_ms) * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": "grouped_gemm_bf16_kernel, both products (weight streaming)",
+                        "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                        "traffic": None, "traffic_source": None, "avg_ms": g1_ms + g2_ms,
+                        "experts_touched": len(touched), "algorithmic_bytes": bytes_ffn,
+                        "mfma_frac_of_peak": (flops1 + flops2) / ((g1_ms + g2_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     else:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -330,6 +351,32 @@ def main():
     }
     hbm["permute_frac"] = hbm["permute_GBs"] / PEAK_HBM_GBS
     hbm["combine_frac"] = hbm["combine_GBs"] / PEAK_HBM_GBS
+    # routing and histogram: algorithmic bytes (logits in, indices and weights out; indices in)
+    # over the call's time.  At the workload's own size both are a few microseconds of traffic
+    # behind a launch, so the same calls are also timed on 2^20 tokens of the same E and k,
+    # where they can show what bandwidth they reach.
+    bytes_route = 4 * cfg.T * cfg.E + 8 * cfg.A
+    bytes_hist = 4 * cfg.A
+    hbm["route_GBs"] = bytes_route / (stage_ms["route"] * 1e-3) / 1e9
+    hbm["route_frac"] = hbm["route_GBs"] / PEAK_HBM_GBS
+    hbm["histogram_GBs"] = bytes_hist / (stage_ms["histogram"] * 1e-3) / 1e9
+    hbm["histogram_frac"] = hbm["histogram_GBs"] / PEAK_HBM_GBS
+    T_big = 1 << 20
+    lg_big = torch.randn((T_big, cfg.E), device="cuda")
+    idx_big = torch.empty((T_big, cfg.k), dtype=torch.int32, device="cuda")
+    w_big = torch.empty((T_big, cfg.k), dtype=torch.float32, device="cuda")
+    hist_big = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
+    time_stage("route_big", lambda: B.moe_route_topk(lg_big, cfg.k, out=(idx_big, w_big)))
+    time_stage("hist_big", lambda: B.moe_histogram(idx_big, cfg.E, out=hist_big))
+    rb, hb = stage_ms.pop("route_big"), stage_ms.pop("hist_big")
+    stage_min_ms.pop("route_big")
+    stage_min_ms.pop("hist_big")
+    hbm["large_T"] = {"T": T_big, "E": cfg.E, "k": cfg.k,
+                      "route_ms": rb, "route_GBs": (4 * T_big * cfg.E + 8 * T_big * cfg.k) / (rb * 1e-3) / 1e9,
+                      "histogram_ms": hb, "histogram_GBs": 4 * T_big * cfg.k / (hb * 1e-3) / 1e9}
+    hbm["large_T"]["route_frac"] = hbm["large_T"]["route_GBs"] / PEAK_HBM_GBS
+    hbm["large_T"]["histogram_frac"] = hbm["large_T"]["histogram_GBs"] / PEAK_HBM_GBS
+    del lg_big, idx_big, w_big, hist_big
 
     # the same two stages with cold caches: a 1 GiB fill between runs pushes the operands out of
     # the L2s and the 256 MB memory-side cache (median of 7 single runs)
@@ -470,22 +517,27 @@ def main():
 
     sweep = plan_sweep()
 
-    # the other row-gather variant, timed the same way (extra, not the headline; the fused
-    # gather exists for the SwiGLU form only)
-    other_key = "six_call_path" if args.fused_gather else "fused_gather_path"
-    other_result = None
+    # the variants with the boundary copies folded into the FFN, timed the same way (extras, not
+    # the headline; built for the SwiGLU form): rows gathered inside the first product, and on
+    # top of that the gate weights applied by the second product with a plain sum in the combine
+    fused = {}
     if cfg.act != "relu":
-        other = MoELayer(cfg, fused_gather=not args.fused_gather)
-        other.packed = layer.packed
-        for _ in range(max(1, args.warmup)):
-            other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
-        torch.cuda.synchronize()
-        other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        other_result = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
+        for key, kw in (("fused_gather_path", dict(fused_gather=True)),
+                        ("fused_gather_and_weights_path", dict(fused_weights=True))):
+            if key == "fused_gather_path" and args.fused_gather:
+                key, kw = "six_call_path", dict()
+            other = MoELayer(cfg, **kw)
+            other.packed = layer.packed
+            for _ in range(max(1, args.warmup)):
+                other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                other.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+            torch.cuda.synchronize()
+            other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            fused[key] = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
+            del other
 
     dense = None
     if args.dense_context and bf16 and cfg.act != "relu":
@@ -495,8 +547,8 @@ def main():
         "dense_context": dense,
         "stage_ms": stage_ms, "stage_min_ms": stage_min_ms, "hbm_stages": hbm, "load": report, "ranks": ranks, "comm": comm,
         "predictor_stream": stream, "plan_sweep": sweep,
-        other_key: other_result,
     })
+    result.update(fused)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, (logits_h, x_h, Ws, hist_pred_h, pred_idx_h, wl))
     if args.stages:
