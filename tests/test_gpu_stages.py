@@ -136,7 +136,10 @@ def test_plan_many_ranks():
 @pytest.mark.parametrize("T,E,k,G,S", [(300, 12, 3, 4, 5), (1, 4, 2, 2, 2), (2049, 8, 1, 8, 2), (5000, 40, 7, 10, 6),
                                        (700, 6, 6, 3, 3), (1000, 128, 16, 32, 5),
                                        (900, 1024, 16, 256, 8),      # the limits: 1024 experts, top-16, 2048 segments
-                                       (3000, 1000, 4, 128, 16)])   # 16 slots per rank
+                                       (3000, 1000, 4, 128, 16),     # 16 slots per rank
+                                       # whole numbers of 2048-assignment chunks and one over; 256 / 257 experts
+                                       (4096, 8, 2, 8, 2), (8192, 8, 1, 8, 2), (8193, 8, 1, 8, 2),
+                                       (512, 256, 16, 64, 4), (512, 257, 16, 64, 5), (2731, 64, 3, 16, 5)])
 def test_permute_small(mode, T, E, k, G, S):
     cfg = wl.MoEConfig("p", T=T, d=16, ffn=8, E=E, k=k, G=G, S=S, dtype="f32", mode=mode, alpha=0.3,
                        sigma_pred=0.3, acc=0.8, seed=T + E)
