@@ -225,6 +225,17 @@ def main():
     hist_pred = None if hist_pred_h is None else torch.from_numpy(hist_pred_h).cuda()
     pred_idx = None if pred_idx_h is None else torch.from_numpy(pred_idx_h).cuda()
 
+    # digests of the generated inputs (the arrays as they go to the device), so that a results line
+    # names exactly the data it was measured on
+    import hashlib
+
+    def digest(a):
+        return None if a is None else hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()[:16]
+
+    input_digests = {"logits": digest(logits_h), "x": digest(wl.to_storage(x_h, cfg.dtype)),
+                     "W1": digest(Ws[0]), "W3": digest(Ws[1]), "W2": digest(Ws[2]),
+                     "hist_pred": digest(hist_pred_h), "pred_idx": digest(pred_idx_h)}
+
     def step():
         return layer.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
 
@@ -304,6 +315,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": describe(cfg), "T": cfg.T, "A": cfg.A, "mode": cfg.mode, "seed": cfg.seed,
+                   "input_sha256": input_digests,
                    "row_gather": "fused into the first FFN product" if args.fused_gather else "x_perm copy (six-call path)"},
         "roofline": roofline,
     }
@@ -538,6 +550,20 @@ def main():
             other_ms = (time.perf_counter() - t0) * 1e3 / args.steps
             fused[key] = {"ms_per_step": other_ms, "value": cfg.T / (other_ms * 1e-3), "unit": "tokens/s"}
             del other
+
+    # the same six calls replayed from a HIP graph (one capture, then replays timed like the steps
+    # above): what the launch gaps between the small kernels cost
+    graph = layer.capture(logits, x, hist_pred=hist_pred, pred_idx=pred_idx)
+    for _ in range(max(1, args.warmup)):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fused["hip_graph_replay"] = {"ms_per_step": g_ms, "value": cfg.T / (g_ms * 1e-3), "unit": "tokens/s"}
+    del graph
 
     dense = None
     if args.dense_context and bf16 and cfg.act != "relu":

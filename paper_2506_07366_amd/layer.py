@@ -132,6 +132,21 @@ class MoELayer:
         self.combine()
         return self.out
 
+    def capture(self, logits: torch.Tensor, x: torch.Tensor, hist_pred: Optional[torch.Tensor] = None,
+                pred_idx: Optional[torch.Tensor] = None, mode: Optional[int] = None):
+        """Records one whole step into a HIP graph and returns it (``graph.replay()`` then runs
+        the step again on whatever the same input tensors hold by then; the result is in
+        ``self.out``).  Every call of the library only enqueues kernels on the current stream and
+        this object owns all buffers, so the step captures as it is: no allocation, no host
+        synchronisation, no memset nodes.  One eager step runs first (it sets the kernels' LDS
+        attribute, which is not a stream operation)."""
+        self.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx, mode=mode)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(logits, x, hist_pred=hist_pred, pred_idx=pred_idx, mode=mode)
+        return graph
+
     def comm_report(self, mode=None, pred_idx: Optional[torch.Tensor] = None, link_GBs: float = 153.6) -> dict:
         """Rows (and bytes) that would cross the emulated ranks at dispatch and combine for the
         last permutation (one C-ABI call + host read-back, off the timed path), next to the

@@ -512,3 +512,54 @@ def test_ffn_workspace_exact_size_accepted_one_byte_less_refused(split, ffn_opti
     assert np.all(np.max(np.abs(y - ref), axis=1) <= TOL["bf16"] * np.max(np.abs(ref)))
     with pytest.raises(B.MoeGpsError):
         B.moe_grouped_ffn(xd, dev_i32(so), dev_i32(slot_expert), packed, cfg.E, cfg.ffn, workspace=ws[:need - 1])
+
+
+def test_ffn_bits_do_not_depend_on_the_order_tiles_are_claimed():
+    """Workgroups claim tiles from counters, so the order varies from run to run; a row's sums
+    do not: ten runs of a Mixtral-shaped batch give the same bytes, split tiles included."""
+    cfg = wl.CONFIGS["cfg2_mixtral_dist"].replace(T=1024)
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    layer = MoELayer(cfg)
+    layer.set_weights(*dev_weights(cfg, Ws))
+    first = None
+    for _ in range(10):
+        out = layer.step(case.dev_logits(), case.dev_x(), hist_pred=case.dev_hist_plan(), pred_idx=case.dev_pred_idx())
+        torch.cuda.synchronize()
+        got = (layer.y_perm.view(torch.int16).clone(), out.view(torch.int16).clone())
+        if first is None:
+            first = got
+        assert torch.equal(got[0], first[0]) and torch.equal(got[1], first[1])
+
+
+@pytest.mark.parametrize("name,mode", [("mid_bf16", 1), ("mid_bf16", 2), ("cfg1_tiny_f32", 1)])
+def test_layer_step_replays_from_a_hip_graph(name, mode):
+    """The whole step captured into a HIP graph: every replay gives the eager step's bytes, also
+    after the inputs were overwritten in place and with eager work and synchronisations between
+    the replays."""
+    cfg = wl.CONFIGS[name].replace(mode=mode, acc=0.9)
+    case = Case(cfg)
+    Ws = host_weights(cfg)
+    dw = dev_weights(cfg, Ws)
+    logits, x = case.dev_logits(), case.dev_x()
+    hp, pi = case.dev_hist_plan(), case.dev_pred_idx()
+    eager = MoELayer(cfg)
+    eager.set_weights(*dw)
+    layer = MoELayer(cfg)
+    layer.set_weights(*dw)
+    graph = layer.capture(logits, x, hist_pred=hp, pred_idx=pi)
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        if rep > 0:   # new token rows and router logits in the captured tensors
+            x.copy_(to_device(wl.to_storage(wl.quantize(rng.standard_normal((cfg.T, cfg.d)).astype(np.float32), cfg.dtype),
+                                            cfg.dtype), cfg.dtype))
+            logits.copy_(torch.from_numpy(rng.standard_normal((cfg.T, cfg.E)).astype(np.float32)).cuda())
+        layer.out.zero_()
+        layer.y_perm.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        ref = eager.step(logits, x, hist_pred=hp, pred_idx=pi)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.topk_idx, eager.topk_idx)
+        assert torch.equal(layer.perm["row_of_assign"], eager.perm["row_of_assign"])
+        assert torch.equal(layer.out.view(torch.uint8), ref.view(torch.uint8)), rep

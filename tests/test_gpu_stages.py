@@ -256,3 +256,34 @@ def test_errors_concentrated_on_one_rank():
     load = worst.perm["rank_load"]
     assert load.argmax() == 0
     assert load.max() > typical.perm["rank_load"].max()
+
+
+# ---------------------------------------------------------------- determinism
+def test_integer_stages_do_not_depend_on_the_launch():
+    """Every integer output is byte-identical from run to run and between batches cut in different
+    ways: no position is decided by an atomic or by arrival order.  The first 3000 tokens of a
+    5000-token batch routed alone give the first 3000 rows of its routing (another grid), the
+    histogram of a concatenation is the sum of the parts' (wide and single-workgroup kernels), and
+    plan and permutation repeat bit for bit."""
+    cfg = wl.MoEConfig("det", T=5000, d=64, ffn=64, E=40, k=7, G=10, S=6, dtype="f32", mode=2, alpha=0.3, acc=0.8,
+                       seed=77)
+    case = Case(cfg)
+    lg = case.dev_logits()
+    idx1, w1 = B.moe_route_topk(lg, cfg.k)
+    idx2, w2 = B.moe_route_topk(lg, cfg.k)
+    assert torch.equal(idx1, idx2) and torch.equal(w1.view(torch.int32), w2.view(torch.int32))
+    idx3, w3 = B.moe_route_topk(lg[:3000].contiguous(), cfg.k)
+    assert torch.equal(idx3, idx1[:3000]) and torch.equal(w3.view(torch.int32), w1[:3000].view(torch.int32))
+    big = idx1.repeat(12, 1)                                        # 420 000 ids: the wide histogram kernel
+    h_big = B.moe_histogram(big, cfg.E)
+    h_one = B.moe_histogram(idx1, cfg.E)                            # 35 000 ids: one workgroup
+    assert torch.equal(h_big, 12 * h_one) and torch.equal(h_one, B.moe_histogram(idx1, cfg.E))
+    pred = case.dev_pred_idx()
+    hp = B.moe_histogram(pred, cfg.E)
+    plans = [B.moe_plan_duplicates(2, hp, cfg.G, cfg.S, cfg.cmax) for _ in range(2)]
+    for a, b in zip(*plans):
+        assert torch.equal(a, b)
+    se, sq = plans[0][0], plans[0][1]
+    outs = [B.moe_permute(2, case.dev_x(), idx1, pred, h_one, hp, se, sq, cfg.E, cfg.G, cfg.S) for _ in range(2)]
+    for key in ("seg_offsets", "row_of_assign", "assign_of_row", "rank_load", "x_perm"):
+        assert torch.equal(outs[0][key].view(torch.uint8), outs[1][key].view(torch.uint8)), key
