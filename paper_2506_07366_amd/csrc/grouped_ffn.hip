@@ -365,6 +365,26 @@ __device__ __forceinline__ void lds_wait() {
 }
 __device__ __forceinline__ void lds_landed(bf16x8& v) { asm volatile("" : "+v"(v)); }
 
+// A copy of a lane-dependent value that the compiler cannot trace back: what is computed
+// from it is computed where it is used (per tile) instead of once per kernel and then kept
+// in a register, or in scratch memory, across the K loop.
+__device__ __forceinline__ int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l's piece comes from
+// base + voff (uniform 64-bit base in scalar registers, 32-bit byte offset per lane: an
+// addressing mode of the instruction, so a load costs no vector ALU work and one address
+// register) and lands at LDS byte address lds_addr + 16 * l (uniform, handed over in M0).
+// Counts on vmcnt like any load.
+__device__ __forceinline__ void global_to_lds_b128(const void* base, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
+
 // two floats rounded to bf16 (nearest even) and packed, low half first: one conversion instruction
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
     typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
@@ -463,37 +483,66 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const int total = n_entries * n_ntiles;
     const int total0 = pass0_end * n_ntiles, total1 = pass1_end * n_ntiles;
     __shared__ volatile int next_tile;
-    int q_done = 0;  // thread 0: counters xcd .. xcd + q_done - 1 (mod 8) have run out
+    // The claims are the business of wavefront 0, and every value involved is the same in
+    // all its lanes, so the state lives in scalar registers (lane 0 performs the atomic, its
+    // result is broadcast): nothing of it occupies a vector register across the K loop
+    // except the pending result of the claim made ahead.
+    int dry = 0;  // bit q set = counter q has run out
     // tile number for claim i of XCD q's counter, -1 if that counter has run out
     auto tile_of_claim = [&](int q, int i) {
         const int t = (q + 8 * (i / run)) * run + i % run;
         return t < total ? t : -1;  // claims only grow: past the end once, past the end for good
     };
-    // thread 0 only: turns a claim made ahead of time (or none: q < 0) into a tile, making
-    // further claims as needed; -1 when every counter has run out
+    // number of claims counter q can serve: its runs are q, q + 8, ... of which the first
+    // total / run are whole and run number total / run holds the remainder
+    auto claims_of = [&](int q) {
+        const int whole = total / run, part = total - whole * run;
+        return (whole > q ? (whole - q + 7) / 8 * run : 0) + ((whole >= q && ((whole - q) & 7) == 0) ? part : 0);
+    };
+    // the counter to claim from next, own XCD first; -1 when all have run out
+    auto next_counter = [&]() {
+        for (int j = 0; j < 8; ++j) {
+            const int q = (xcd + j) & 7;
+            if (!((dry >> q) & 1)) return q;
+        }
+        return -1;
+    };
+    auto claim_from = [&](int q) {  // one claim, result not yet waited for (lane 0 holds it)
+        int r = 0;
+        if (lane == 0) r = atomicAdd(&queues[q], 1);
+        return r;
+    };
+    // Turns a claim made ahead of time (or none: q < 0) into a tile, making further claims as
+    // needed; -1 when every counter has run out.  Once a claim has come back empty all eight
+    // counters are read in one go (one round trip, not one per counter), and those that stand
+    // at their limit are struck off.
     auto settle_claim = [&](int q, int i) {
         for (;;) {
             if (q >= 0) {
                 const int t = tile_of_claim(q, i);
                 if (t >= 0) return t;
-                if (q == ((xcd + q_done) & 7)) ++q_done;
+                dry |= 1 << q;
+                const int seen = __hip_atomic_load(&queues[lane & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    if (__builtin_amdgcn_readlane(seen, c) >= claims_of(c)) dry |= 1 << c;
             }
-            if (q_done >= 8) return -1;
-            q = (xcd + q_done) & 7;
-            i = atomicAdd(&queues[q], 1);
+            q = next_counter();
+            if (q < 0) return -1;
+            i = __builtin_amdgcn_readfirstlane(claim_from(q));
         }
     };
-    if (tid == 0) next_tile = settle_claim(-1, 0);
+    if (wave == 0) next_tile = settle_claim(-1, 0);
     for (;;) {
         lds_wait<0>();                 // thread 0's store of next_tile
         __builtin_amdgcn_s_barrier();  // also: every wavefront is done reading the previous tile's stages
         const int t_all = __builtin_amdgcn_readfirstlane(next_tile);
         if (t_all < 0) break;
         // the claim for the tile after this one is made now and looked at after the K loop
-        int ahead_q = -1, ahead_i = 0;
-        if (tid == 0 && q_done < 8) {
-            ahead_q = (xcd + q_done) & 7;
-            ahead_i = atomicAdd(&queues[ahead_q], 1);
+        int ahead_q = -1, ahead_pending = 0;
+        if (wave == 0) {
+            ahead_q = next_counter();
+            if (ahead_q >= 0) ahead_pending = claim_from(ahead_q);
         }
         const int pass = t_all < total0 ? 0 : (t_all < total1 ? 1 : 2);
         const int t = pass == 0 ? t_all : (pass == 1 ? t_all - total0 : t_all - total1);
@@ -520,9 +569,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // dropped in the epilogue).  (uniform base) + (32-bit lane offset) is an addressing
         // mode of the load instruction, so the loads spend no vector ALU work on addresses.
         unsigned offA_b[IAW], offB_b[IBW];
+        const int lane_p = opaque(lane);
 #pragma unroll
         for (int i = 0; i < IAW; ++i) {
-            const int p = (wave + i * NW) * 64 + lane;
+            const int p = (wave + i * NW) * 64 + lane_p;
             const int row = p / CPR, slot = p % CPR;
             int r = row < mt.rows ? row : mt.rows - 1;
             if (rm.a_rows) {
@@ -533,28 +583,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         }
 #pragma unroll
         for (int i = 0; i < IBW; ++i) {
-            const int p = (wave + i * NW) * 64 + lane;
+            const int p = (wave + i * NW) * 64 + lane_p;
             const int row = p / CPR, slot = p % CPR;
             const int r = row < n_valid ? row : n_valid - 1;
             offB_b[i] = ((unsigned)r * (unsigned)K + (unsigned)((slot ^ swz(row)) * 8)) * 2u;
         }
 
         // load l of this wavefront's LPT loads of k-tile kt (activations first), one instruction
+        const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+        const unsigned lds_wave = lds_base + (unsigned)wave * 1024u;
         auto issue_load_n = [&](auto L, int kt, int stage) {
             constexpr int l = decltype(L)::value;
-            unsigned char* sA = smem + stage * STAGE_BYTES;
+            const unsigned sA = lds_wave + (unsigned)(stage * STAGE_BYTES);
             if constexpr (l < IAW) {
                 const unsigned char* base = (const unsigned char*)Ab + (size_t)(kt * (BK * 2));
                 if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(base + (size_t)offA_b[l]),
-                        (__attribute__((address_space(3))) void*)(sA + (wave + l * NW) * 1024), 16, 0, 0);
+                    global_to_lds_b128(base, offA_b[l], sA + (unsigned)(l * NW * 1024));
             } else {
                 const unsigned char* base = (const unsigned char*)Bb + (size_t)(kt * (BK * 2));
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(base + (size_t)offB_b[l - IAW]),
-                    (__attribute__((address_space(3))) void*)(sA + A_BYTES + (wave + (l - IAW) * NW) * 1024), 16,
-                    0, 0);
+                global_to_lds_b128(base, offB_b[l - IAW], sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
             }
         };
         auto issue_loads = [&](int kt, int stage) {
@@ -579,8 +626,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             for (int j = 0; j < TN16; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc16[i][j][r] = 0.f;
-        const int l16 = lane & 15, g16 = lane >> 4;
-        const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+        const int lane_k = opaque(lane);
+        const int l16 = lane_k & 15, g16 = lane_k >> 4;
 
         // K loop.  A step is 32 deep: TM16 activation fragments (16 rows each) and TN16 weight
         // fragments, TM16 * TN16 MFMAs, taken row of tiles by row of tiles.  The weight
@@ -696,9 +743,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         else
             k_loop16(std::false_type{});
         // every wavefront has read next_tile (the K loop holds a barrier)
-        if (tid == 0) next_tile = settle_claim(ahead_q, ahead_i);
+        if (wave == 0) next_tile = settle_claim(ahead_q, __builtin_amdgcn_readfirstlane(ahead_pending));
 
         // epilogue: 4 consecutive columns per lane and tile -> 8-byte stores (16 bytes of fp32 partial sums)
+        const int lane_e = opaque(lane);
+        const int l16e = lane_e & 15, g16e = lane_e >> 4;
         const int n_out = SWIGLU ? N / 2 : N;
         const int col0 = (SWIGLU ? (n0 + wn * WTN) / 2 : (n0 + wn * WTN));
         constexpr int TNO16 = SWIGLU ? TN16 / 2 : TN16;  // 16-column tiles of output per wavefront
@@ -706,19 +755,38 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         float* slab = nullptr;
         if constexpr (EPI == kEpiNone)
             if (mt.part >= 0) slab = partials + (size_t)mt.part * kPartRows * N;
+        // output row and scale of this lane's TM16 rows, fetched as one batch (row by row each
+        // would wait out a memory round trip, and with it the stores of the row before)
+        int crow_of[TM16];
+        float sc_of[TM16];
 #pragma unroll
         for (int i = 0; i < TM16; ++i) {
-            const int row = wm * WTM + i * 16 + l16;
-            if (row < mt.rows) {
-                int crow_i = mt.list0 + row;
-                float sc = 1.0f;
-                if constexpr (EPI == kEpiNone) {
-                    if (!slab) {
-                        if (rm.c_rows) crow_i = rm.c_rows[crow_i];
-                        if (rm.scale) sc = rm.scale[rm.scale_idx[crow_i]];
-                    }
+            const int row = wm * WTM + i * 16 + l16e;
+            crow_of[i] = mt.list0 + (row < mt.rows ? row : mt.rows - 1);
+            sc_of[i] = 1.0f;
+        }
+        if constexpr (EPI == kEpiNone) {
+            if (!slab) {
+                if (rm.c_rows) {
+#pragma unroll
+                    for (int i = 0; i < TM16; ++i) crow_of[i] = rm.c_rows[crow_of[i]];
                 }
-                bf16_t* crow = C + (size_t)crow_i * ldc + col0 + g16 * 4;
+                if (rm.scale) {
+                    int si[TM16];
+#pragma unroll
+                    for (int i = 0; i < TM16; ++i) si[i] = rm.scale_idx[crow_of[i]];
+#pragma unroll
+                    for (int i = 0; i < TM16; ++i) sc_of[i] = rm.scale[si[i]];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TM16; ++i) {
+            const int row = wm * WTM + i * 16 + l16e;
+            if (row < mt.rows) {
+                const int crow_i = crow_of[i];
+                const float sc = sc_of[i];
+                bf16_t* crow = C + (size_t)crow_i * ldc + col0 + g16e * 4;
 #pragma unroll
                 for (int jo = 0; jo < TNO16; ++jo) {
                     // output tile jo: packed tiles (jo/2)*4 + jo%2 (gate) and + 2 (up) with SwiGLU
@@ -740,7 +808,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                             o.y = v[1];
                             o.z = v[2];
                             o.w = v[3];
-                            *(float4*)(slab + (size_t)row * N + col0 + jo * 16 + g16 * 4) = o;
+                            *(float4*)(slab + (size_t)row * N + col0 + jo * 16 + g16e * 4) = o;
                         } else {
                             if constexpr (EPI == kEpiNone) {
 #pragma unroll
