@@ -373,6 +373,15 @@ __device__ __forceinline__ int opaque(int v) {
     return v;
 }
 
+// With the wavefront seen as four quarters of 16 lanes, p = [p0 p1 p2 p3] and q = [q0 q1 q2 q3]
+// become p = [p0 p2 q0 q2] and q = [p1 p3 q1 q3] (two register-to-register swap instructions).
+__device__ __forceinline__ void lane_swap_pairs(unsigned& p, unsigned& q) {
+    auto r = __builtin_amdgcn_permlane32_swap(p, q, false, false);  // p: [p0 p1 q0 q1], q: [p2 p3 q2 q3]
+    auto t = __builtin_amdgcn_permlane16_swap(r[0], r[1], false, false);
+    p = t[0];
+    q = t[1];
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane l's piece comes from
 // base + voff (uniform 64-bit base in scalar registers, 32-bit byte offset per lane: an
 // addressing mode of the instruction, so a load costs no vector ALU work and one address
@@ -780,45 +789,68 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                 }
             }
         }
+        // values of output tile jo (16 columns) of row block i for this lane: 4 consecutive columns
+        auto tile_values = [&](int i, int jo, float sc, float (&v)[4]) {
+            // output tile jo: packed tiles (jo/2)*4 + jo%2 (gate) and + 2 (up) with SwiGLU
+            const int jg = SWIGLU ? (jo / 2) * 4 + (jo % 2) : jo;
 #pragma unroll
-        for (int i = 0; i < TM16; ++i) {
-            const int row = wm * WTM + i * 16 + l16e;
-            if (row < mt.rows) {
-                const int crow_i = crow_of[i];
-                const float sc = sc_of[i];
-                bf16_t* crow = C + (size_t)crow_i * ldc + col0 + g16e * 4;
+            for (int c = 0; c < 4; ++c) {
+                if (SWIGLU)
+                    v[c] = silu_f(acc16[i][jg][c]) * acc16[i][jg + 2][c];
+                else if (EPI == kEpiRelu)
+                    v[c] = fmaxf(acc16[i][jg][c], 0.f);
+                else
+                    v[c] = acc16[i][jg][c] * sc;
+            }
+        };
+        if (slab) {
 #pragma unroll
-                for (int jo = 0; jo < TNO16; ++jo) {
-                    // output tile jo: packed tiles (jo/2)*4 + jo%2 (gate) and + 2 (up) with SwiGLU
-                    const int jg = SWIGLU ? (jo / 2) * 4 + (jo % 2) : jo;
-                    if (col0 + jo * 16 < n_out) {
-                        float v[4];
+            for (int i = 0; i < TM16; ++i) {
+                const int row = wm * WTM + i * 16 + l16e;
+                if (row < mt.rows) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            if (SWIGLU)
-                                v[c] = silu_f(acc16[i][jg][c]) * acc16[i][jg + 2][c];
-                            else if (EPI == kEpiRelu)
-                                v[c] = fmaxf(acc16[i][jg][c], 0.f);
-                            else
-                                v[c] = acc16[i][jg][c];
-                        }
-                        if (slab) {
+                    for (int jo = 0; jo < TNO16; ++jo)
+                        if (col0 + jo * 16 < n_out) {
+                            float v[4];
+                            tile_values(i, jo, 1.0f, v);
                             float4 o;
                             o.x = v[0];
                             o.y = v[1];
                             o.z = v[2];
                             o.w = v[3];
                             *(float4*)(slab + (size_t)row * N + col0 + jo * 16 + g16e * 4) = o;
-                        } else {
-                            if constexpr (EPI == kEpiNone) {
-#pragma unroll
-                                for (int c = 0; c < 4; ++c) v[c] *= sc;
-                            }
-                            uint2 o;
-                            o.x = pack_bf16x2(v[0], v[1]);
-                            o.y = pack_bf16x2(v[2], v[3]);
-                            *(uint2*)(crow + jo * 16) = o;
                         }
+                }
+            }
+        } else {
+            // Rounded to bf16 a lane holds 8 bytes of a row per output tile.  Two tiles side by
+            // side are regrouped with the two lane-swap instructions (quarter q of the wavefront
+            // = lanes 16q .. 16q+15, all of one row set): swapping the upper half of the first
+            // tile's register with the lower half of the second's, then the odd quarters of the
+            // first with the even quarters of the second, leaves quarter q with columns 8q .. 8q+3
+            // of the 32 in the first register and 8q+4 .. 8q+7 in the second: 16 bytes in a row
+            // per lane, half as many store instructions, each writing 64-byte pieces.
+            static_assert(TNO16 % 2 == 0, "output tiles are stored in pairs");
+#pragma unroll
+            for (int i = 0; i < TM16; ++i) {
+                const int row = wm * WTM + i * 16 + l16e;
+                bf16_t* crow = C + (size_t)crow_of[i] * ldc + col0 + g16e * 8;
+#pragma unroll
+                for (int jo = 0; jo < TNO16; jo += 2) {
+                    float v0[4], v1[4];
+                    tile_values(i, jo, sc_of[i], v0);
+                    tile_values(i, jo + 1, sc_of[i], v1);
+                    unsigned px = pack_bf16x2(v0[0], v0[1]), py = pack_bf16x2(v0[2], v0[3]);
+                    unsigned qx = pack_bf16x2(v1[0], v1[1]), qy = pack_bf16x2(v1[2], v1[3]);
+                    lane_swap_pairs(px, qx);
+                    lane_swap_pairs(py, qy);
+                    if (row < mt.rows && col0 + jo * 16 < n_out) {
+                        uint4 o;
+                        o.x = px;
+                        o.y = py;
+                        o.z = qx;
+                        o.w = qy;
+                        *(uint4*)(crow + jo * 16) = o;
                     }
                 }
             }
