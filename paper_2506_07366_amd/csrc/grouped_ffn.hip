@@ -298,6 +298,12 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
             ts.splits[split_index].list0 = list0;
             ts.splits[split_index].rows = rows;
         };
+        // whole ragged tiles of the experts below e (each sits right behind its expert's full tiles)
+        auto whole_tails_below = [&](int e) {
+            int n = 0;
+            for (int j = 0; j < e; ++j) n += (e_tail[j] > 0 && e_rank[j] < n_whole_tail) ? 1 : 0;
+            return n;
+        };
         if (fits) {
             // full-height tiles: tile t belongs to the expert whose range of tile numbers holds it
             for (int t = tid; t < n_full; t += blockDim.x) {
@@ -308,7 +314,7 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
                     else hi = mid - 1;
                 }
                 const int list0 = e_rows[lo] + (t - e_full[lo]) * BM;
-                if (t < n_whole_full) emit(list0, BM, lo, t, -1);
+                if (t < n_whole_full) emit(list0, BM, lo, t + whole_tails_below(lo), -1);
                 else emit(list0, BM, lo, 0, t - n_whole_full);
             }
             // ragged tiles, tallest first (ties: lower expert first); the last n_rsplit of them are split
@@ -318,12 +324,12 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
                 const int rank = e_rank[e];
                 const int list0 = e_rows[e] + (e_full[e + 1] - e_full[e]) * BM;
                 if (rank >= n_whole_tail) emit(list0, tl, e, 0, n_fsplit + rank - n_whole_tail);
-                else emit(list0, tl, e, n_whole_full + rank, -1);
+                else emit(list0, tl, e, (e_full[e + 1] < n_whole_full ? e_full[e + 1] : n_whole_full) + whole_tails_below(e), -1);
             }
         }
         if (tid == 0) {
             ts.counts[kCntEntries] = fits ? n_entries : 0;
-            ts.counts[kCntPass0] = fits ? n_whole_full : 0;
+            ts.counts[kCntPass0] = fits ? n_whole : 0;
             ts.counts[kCntPass1] = fits ? n_whole : 0;
             ts.counts[kCntSplit] = fits ? n_split : 0;
         }
