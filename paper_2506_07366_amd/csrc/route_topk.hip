@@ -1,50 +1,57 @@
 // Gate top-k: the token->expert map f of Algorithm 1 (Background: tokens are
 // routed to their top-K experts).  A group of LPT lanes of a 64-wide wavefront
 // owns one token; every lane keeps VPL logits in registers and the k winners are
-// found by k rounds of a cross-lane arg-max (DPP lane permutes inside a row of 16
-// lanes; a group is at most one such row up to 512 experts).  Order is (logit
-// descending, expert index ascending), so equal logits go to the lowest index.
+// found by k rounds of a cross-lane maximum and a cross-lane minimum over the indices that
+// hold it (DPP lane permutes inside a row of 16 lanes; a group is at most one such row up to
+// 512 experts).  Order is (logit descending, expert index ascending), so equal logits go to
+// the lowest index.
 // Gate weights are a softmax over the k selected logits.
 #include "common.h"
 
 namespace moegps {
 
-// true if (bv, be) comes before (av, ae) in (value descending, index ascending) order
-__device__ __forceinline__ bool better(float bv, int be, float av, int ae) {
-    return (bv > av) || (bv == av && be < ae);
-}
-
 // One butterfly level with a lane permute that stays inside the vector ALU (no LDS
-// crossbar): every lane keeps the better of its own candidate and its partner's.
+// crossbar): every lane keeps the larger value / the smaller index of itself and its partner.
 template <int CTRL>
-__device__ __forceinline__ void dpp_level(float& v, int& e) {
-    const float ov =
+__device__ __forceinline__ float dpp_max(float v) {
+    const float o =
         __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
-    const int oe = __builtin_amdgcn_update_dpp(0, e, CTRL, 0xf, 0xf, false);
-    const bool take = better(ov, oe, v, e);
-    v = take ? ov : v;
-    e = take ? oe : e;
+    return fmaxf(v, o);
 }
-template <int MASK>
-__device__ __forceinline__ void shfl_level(float& v, int& e) {
-    const float ov = __shfl_xor(v, MASK, kWave);
-    const int oe = __shfl_xor(e, MASK, kWave);
-    const bool take = better(ov, oe, v, e);
-    v = take ? ov : v;
-    e = take ? oe : e;
+template <int CTRL>
+__device__ __forceinline__ int dpp_min(int e) {
+    const int o = __builtin_amdgcn_update_dpp(0, e, CTRL, 0xf, 0xf, false);
+    return o < e ? o : e;
 }
 
-// Best candidate of each group of LPT consecutive lanes, known to all its lanes.
-// Inside a row of 16 lanes: quad permutes, then the half-row and row mirrors; across
-// rows one or two shuffles.
+// Largest value / smallest index of each group of LPT consecutive lanes, known to all its
+// lanes.  Inside a row of 16 lanes: quad permutes, then the half-row and row mirrors;
+// across rows one or two shuffles.
 template <int LPT>
-__device__ __forceinline__ void group_best(float& v, int& e) {
-    if constexpr (LPT >= 2) dpp_level<0xB1>(v, e);    // quad_perm [1,0,3,2]
-    if constexpr (LPT >= 4) dpp_level<0x4E>(v, e);    // quad_perm [2,3,0,1]
-    if constexpr (LPT >= 8) dpp_level<0x141>(v, e);   // row_half_mirror
-    if constexpr (LPT >= 16) dpp_level<0x140>(v, e);  // row_mirror
-    if constexpr (LPT >= 32) shfl_level<16>(v, e);
-    if constexpr (LPT == 64) shfl_level<32>(v, e);
+__device__ __forceinline__ float group_max(float v) {
+    if constexpr (LPT >= 2) v = dpp_max<0xB1>(v);    // quad_perm [1,0,3,2]
+    if constexpr (LPT >= 4) v = dpp_max<0x4E>(v);    // quad_perm [2,3,0,1]
+    if constexpr (LPT >= 8) v = dpp_max<0x141>(v);   // row_half_mirror
+    if constexpr (LPT >= 16) v = dpp_max<0x140>(v);  // row_mirror
+    if constexpr (LPT >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    if constexpr (LPT == 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+template <int LPT>
+__device__ __forceinline__ int group_min(int e) {
+    if constexpr (LPT >= 2) e = dpp_min<0xB1>(e);
+    if constexpr (LPT >= 4) e = dpp_min<0x4E>(e);
+    if constexpr (LPT >= 8) e = dpp_min<0x141>(e);
+    if constexpr (LPT >= 16) e = dpp_min<0x140>(e);
+    if constexpr (LPT >= 32) {
+        const int o = __shfl_xor(e, 16, kWave);
+        e = o < e ? o : e;
+    }
+    if constexpr (LPT == 64) {
+        const int o = __shfl_xor(e, 32, kWave);
+        e = o < e ? o : e;
+    }
+    return e;
 }
 
 // LPT lanes own one token; lane `sub` of the group keeps the VPL consecutive logits
@@ -58,7 +65,6 @@ template <int LPT, int VPL>
 __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ logits, int T, int E,
                                                           int k, int32_t* __restrict__ topk_idx,
                                                           float* __restrict__ topk_w) {
-    static_assert(VPL <= 32, "one bit per logit of a lane");
     constexpr int TPW = kWave / LPT;  // tokens per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -90,28 +96,28 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
         for (int i = 0; i < VPL; ++i) v[i] = (e0 + i < E) ? row[e0 + i] : NEG_INF;
     }
 
-    unsigned taken = 0;
+    // Round j: the largest remaining logit of the group (a lane maximum, then a maximum across
+    // the lanes), then the lowest index among the logits that equal it (equal logits go to the
+    // lowest expert), then that logit leaves the game as minus infinity.  Padding columns are
+    // minus infinity from the start and can only come up once every real logit is gone, which
+    // k <= E rules out.
     float l0 = 0.f, my_v = 0.f;
     int my_e = 0;
     for (int j = 0; j < k; ++j) {
-        // best remaining candidate of this lane; padding columns carry their own
-        // (out of range) index and so lose every tie against a real expert
-        float bv = NEG_INF;
-        int be = 0x7fffffff;
+        float m = v[0];
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int ce = e0 + i;
-            const bool take = !((taken >> i) & 1u) && better(v[i], ce, bv, be);
-            bv = take ? v[i] : bv;
-            be = take ? ce : be;
-        }
-        group_best<LPT>(bv, be);
-        // the owner retires the winner
-        if (be / VPL == sub) taken |= 1u << (be % VPL);
-        if (j == 0) l0 = bv;
+        for (int i = 1; i < VPL; ++i) m = fmaxf(m, v[i]);
+        const float g = group_max<LPT>(m);
+        int cand = 0x7fffffff;
+#pragma unroll
+        for (int i = VPL - 1; i >= 0; --i) cand = (v[i] == g) ? e0 + i : cand;
+        const int w = group_min<LPT>(cand);
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) v[i] = (e0 + i == w) ? NEG_INF : v[i];
+        if (j == 0) l0 = g;
         if (sub == j) {
-            my_v = bv;
-            my_e = be;
+            my_v = g;
+            my_e = w;
         }
     }
     const float ex = sub < k ? expf(my_v - l0) : 0.f;
