@@ -57,6 +57,7 @@ struct MTile {
 struct SplitInfo {
     int list0, rows;
 };
+constexpr int kGemmGrid = 256;  // persistent workgroups of a GEMM launch: 8 XCDs x 32
 constexpr int kPartRows = 256;  // rows of one slab of partial sums (the tallest tile shape)
 constexpr int kMaxParts = 4;    // parts of K of a split tile
 
@@ -378,6 +379,11 @@ __device__ __forceinline__ int opaque(int v) {
     asm volatile("" : "+v"(v));
     return v;
 }
+// the same for a value that is uniform over the wavefront (scalar register)
+__device__ __forceinline__ int opaque_uniform(int v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
 
 // With the wavefront seen as four quarters of 16 lanes, p = [p0 p1 p2 p3] and q = [q0 q1 q2 q3]
 // become p = [p0 p2 q0 q2] and q = [p1 p3 q1 q3] (two register-to-register swap instructions).
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     // through the memory-side cache).  A workgroup whose own XCD has no tile left claims from
     // the other XCDs' counters.
     const int xcd = blockIdx.x & 7;
-    const int run = (int)(gridDim.x >> 3);
+    constexpr int run = kGemmGrid / 8;  // the launch is always kGemmGrid workgroups
     const int total = n_entries * n_ntiles;
     const int total0 = pass0_end * n_ntiles, total1 = pass1_end * n_ntiles;
     __shared__ volatile int next_tile;
@@ -510,7 +516,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     };
     // number of claims counter q can serve: its runs are q, q + 8, ... of which the first
     // total / run are whole and run number total / run holds the remainder
-    auto claims_of = [&](int q) {
+    auto claims_of = [&](int q, int total) {  // (total handed in opaque: worked out only when needed)
         const int whole = total / run, part = total - whole * run;
         return (whole > q ? (whole - q + 7) / 8 * run : 0) + ((whole >= q && ((whole - q) & 7) == 0) ? part : 0);
     };
@@ -537,10 +543,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                 const int t = tile_of_claim(q, i);
                 if (t >= 0) return t;
                 dry |= 1 << q;
-                const int seen = __hip_atomic_load(&queues[lane & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int seen = __hip_atomic_load(&queues[opaque(lane) & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int total_now = opaque_uniform(total);
 #pragma unroll
                 for (int c = 0; c < 8; ++c)
-                    if (__builtin_amdgcn_readlane(seen, c) >= claims_of(c)) dry |= 1 << c;
+                    if (__builtin_amdgcn_readlane(seen, c) >= claims_of(c, total_now)) dry |= 1 << c;
             }
             q = next_counter();
             if (q < 0) return -1;
@@ -592,7 +599,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             int r = row < mt.rows ? row : mt.rows - 1;
             if (rm.a_rows) {
                 r = rm.a_rows[mt.list0 + r];
-                if (rm.a_rows2) r = rm.a_rows2[r] / rm.a_div;
+                if (rm.a_rows2) r = rm.a_rows2[r] / opaque_uniform(rm.a_div);
             }
             offA_b[i] = ((unsigned)r * (unsigned)lda + (unsigned)((slot ^ swz(row)) * 8)) * 2u;
         }
@@ -1008,7 +1015,6 @@ struct FfnWs {
 };
 
 constexpr int kMinBM = 64;
-constexpr int kGemmGrid = 256;  // persistent workgroups: 8 XCDs x 32
 
 // Process-wide overrides of the automatic choices (moe_grouped_ffn_set_option); -1 / 0 = automatic.
 static std::atomic<int> g_opt_tile1{-1}, g_opt_tile2{-1}, g_opt_split{-1}, g_opt_group_n{0};
