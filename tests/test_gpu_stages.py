@@ -43,6 +43,27 @@ def test_route_ties_lowest_index():
         assert np.max(np.abs(w.cpu().numpy() - rw)) <= 1e-6
 
 
+def test_route_signed_zeros_denormals_and_k_equal_E():
+    """Values that compare equal without being the same bits (+0 and -0), values below the normal
+    range, very large magnitudes and k = E (every logit is taken once, none twice)."""
+    rng = np.random.default_rng(7)
+    for E, k in [(8, 8), (16, 16), (24, 16), (128, 8), (64, 6), (5, 3), (32, 16), (3, 3)]:
+        logits = rng.standard_normal((300, E)).astype(np.float32)
+        zero_mask = rng.random((300, E)) < 0.4
+        logits[zero_mask] = np.where(rng.random(int(zero_mask.sum())) < 0.5, np.float32(0.0), np.float32(-0.0))
+        tiny = rng.random((300, E)) < 0.2
+        logits[tiny] = (rng.integers(-6, 7, int(tiny.sum())) * np.float32(1e-41)).astype(np.float32)  # subnormal steps
+        logits[1, :] = np.float32(-0.0)
+        logits[2, :] = np.float32(-3.0e38)
+        logits[3, : E // 2] = np.float32(3.0e38)
+        idx, w = B.moe_route_topk(torch.from_numpy(logits).cuda(), k)
+        ridx, rw = route_topk(logits, k)
+        got = idx.cpu().numpy()
+        assert np.array_equal(got, ridx), (E, k)
+        assert all(len(set(r)) == k for r in got)
+        assert np.max(np.abs(w.cpu().numpy().astype(np.float64) - rw)) <= 1e-6
+
+
 @pytest.mark.parametrize("name", INT_CFGS)
 def test_integer_stages_on_config(name):
     """route, histogram, plan and permutation on the full-size seeded workload."""
