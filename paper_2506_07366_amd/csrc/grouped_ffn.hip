@@ -1022,6 +1022,14 @@ static std::atomic<int> g_opt_tile1{-1}, g_opt_tile2{-1}, g_opt_split{-1}, g_opt
 // The bf16 kernels work on a hidden width padded to a multiple of 64: the packed weights
 // carry zero columns (W1, W3) and zero rows (W2) for the padding, so the padded hidden
 // activations are exact zeros and add nothing to the second product.
+// Widths above this are refused: it keeps every size computed on the host inside 64 bits and
+// every tile offset computed on the device inside 32.
+constexpr int kMaxWidth = 1 << 22;
+static inline bool ffn_shape_in_range(int64_t A, int d, int ffn, int nseg, int dtype) {
+    return (dtype == MOE_DTYPE_F32 || dtype == MOE_DTYPE_BF16) && A >= 0 && A < (1ll << 31) && d >= 1 &&
+           d <= kMaxWidth && ffn >= 1 && ffn <= kMaxWidth && nseg >= 1 && nseg <= MOE_MAX_SEGMENTS;
+}
+
 static inline int padded_ffn(int ffn, int dtype) {
     return dtype == MOE_DTYPE_BF16 ? (int)align_up((size_t)ffn, 64) : ffn;
 }
@@ -1178,7 +1186,7 @@ extern "C" int moe_grouped_ffn_set_option(int option, int value) {
 }
 
 extern "C" size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype) {
-    if (E < 1 || d < 1 || ffn < 1) return 0;
+    if (E < 1 || E > MOE_MAX_EXPERTS || !moegps::ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
     return (size_t)3 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
 }
 
@@ -1236,7 +1244,7 @@ extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, 
 }
 
 extern "C" size_t moe_packed_weights_relu_bytes(int E, int d, int ffn, int dtype) {
-    if (E < 1 || d < 1 || ffn < 1) return 0;
+    if (E < 1 || E > MOE_MAX_EXPERTS || !moegps::ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
     return (size_t)2 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
 }
 
@@ -1247,7 +1255,7 @@ extern "C" int moe_pack_weights_relu(const void* W1, const void* W2, int dtype, 
 
 extern "C" size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype) {
     using namespace moegps;
-    if (A < 0 || d < 1 || ffn < 1 || nseg < 1) return 0;
+    if (!ffn_shape_in_range(A, d, ffn, nseg, dtype)) return 0;
     return ffn_ws_layout(A, d, ffn, nseg, dtype, nullptr, nullptr);
 }
 
@@ -1266,6 +1274,7 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     if (A < 0 || d < 1 || ffn < 1 || E < 1 || nseg < 1) return MOE_ERR_INVALID_ARG;
     if (seg_begin < 0 || seg_end > nseg || seg_begin > seg_end) return MOE_ERR_INVALID_ARG;
     if (nseg > MOE_MAX_SEGMENTS || E > MOE_MAX_EXPERTS || A >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    if (d > kMaxWidth || ffn > kMaxWidth) return MOE_ERR_UNSUPPORTED;
     if (dtype == MOE_DTYPE_BF16 && d % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (dtype == MOE_DTYPE_F32 && (d % 4 != 0 || ffn % 4 != 0)) return MOE_ERR_UNSUPPORTED;
     if ((int64_t)256 * (d > ffn + 63 ? d : ffn + 63) >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;  // 32-bit tile offsets

@@ -390,6 +390,9 @@ __global__ __launch_bounds__(256) void perm_scatter_rows_kernel(const uint4* __r
 extern "C" size_t moe_permute_workspace_bytes(int T, int E, int k, int G, int S) {
     using namespace moegps;
     if (T < 0 || E < 1 || k < 1 || G < 1 || S < 1) return 0;
+    if (E > MOE_MAX_EXPERTS || k > MOE_MAX_TOPK || G > MOE_MAX_RANKS || S > MOE_MAX_SLOTS || G * S > MOE_MAX_SEGMENTS ||
+        (int64_t)T * k >= (1ll << 31))
+        return 0;
     return perm_ws_layout(T, E, k, G, S, nullptr, nullptr);
 }
 
@@ -402,10 +405,10 @@ static int permute_impl(int mode, const void* x, int dtype, int T, int d, int E,
     if (mode < MOE_MODE_NONE || mode > MOE_MODE_TOKEN) return MOE_ERR_INVALID_ARG;
     if (dtype != MOE_DTYPE_F32 && dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
     if (T < 0 || d < 1 || E < 1 || k < 1 || k > E || G < 1 || S < 1) return MOE_ERR_INVALID_ARG;
-    if ((E + G - 1) / G > S) return MOE_ERR_INVALID_ARG;
     if (E > MOE_MAX_EXPERTS || k > MOE_MAX_TOPK || G > MOE_MAX_RANKS || S > MOE_MAX_SLOTS ||
         G * S > MOE_MAX_SEGMENTS)
         return MOE_ERR_UNSUPPORTED;
+    if (ceil_div(E, G) > S) return MOE_ERR_INVALID_ARG;
     if ((int64_t)T * k >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
     if (((size_t)d * dtype_size(dtype)) % 16 != 0) return MOE_ERR_UNSUPPORTED;
     if (!seg_offsets || !rank_load || !slot_expert || !slot_quota || !workspace) return MOE_ERR_INVALID_ARG;

@@ -314,7 +314,7 @@ extern "C" int moe_plan_duplicates(int mode, const int32_t* hist_pred, int E, in
     using namespace moegps;
     if (mode < MOE_MODE_NONE || mode > MOE_MODE_TOKEN) return MOE_ERR_INVALID_ARG;
     if (E < 1 || G < 1 || S < 1 || c_max < 1) return MOE_ERR_INVALID_ARG;
-    if ((E + G - 1) / G > S) return MOE_ERR_INVALID_ARG;  // every expert needs a home slot
+    if (ceil_div(E, G) > S) return MOE_ERR_INVALID_ARG;  // every expert needs a home slot
     if (E > MOE_MAX_EXPERTS || G > MOE_MAX_RANKS || S > MOE_MAX_SLOTS || G * S > MOE_MAX_SEGMENTS)
         return MOE_ERR_UNSUPPORTED;
     if (!hist_pred || !slot_expert || !slot_quota || !rank_load_pred || !n_iters) return MOE_ERR_INVALID_ARG;
