@@ -132,7 +132,8 @@ int moe_plan_duplicates(int mode, const int32_t* hist_pred, int E, int G, int S,
  *   x_perm        [A, d]  dtype out  x_perm[row] = x[assign_of_row[row] / k]; may be
  *                                    NULL to skip the row copy
  *   rank_load     [G]     int32 out  rows served by each rank
- * d * sizeof(dtype) must be a multiple of 16.  A < 2^31.
+ * d * sizeof(dtype) must be a multiple of 16.  A < 2^31.  The size query returns 0 for
+ * arguments outside the limits above (MOE_MAX_*).
  */
 size_t moe_permute_workspace_bytes(int T, int E, int k, int G, int S);
 int moe_permute(int mode, const void* x, int dtype, int T, int d, int E, int k, int G, int S,
@@ -198,6 +199,8 @@ int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,
  * order of the parts, then rounded once); the result does not depend on launch order.
  * bf16 needs d % 64 == 0 (any ffn: the packed weights pad the hidden width to a multiple of
  * 64 with zeros) and A * d < 2^31; f32 needs d % 4 == 0 and ffn % 4 == 0.
+ * Limits: 0 <= A < 2^31, 1 <= d, ffn <= 2^22, 1 <= nseg <= MOE_MAX_SEGMENTS.  The size query
+ * returns 0 for arguments outside them (every size query of this library does).
  */
 size_t moe_grouped_ffn_workspace_bytes(int64_t A, int d, int ffn, int nseg, int dtype);
 int moe_grouped_ffn(const void* x_perm, int dtype, int64_t A, int d, int ffn, int E,
