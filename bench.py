@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "9d03f93654ebe690a7eae53d590ed3185df203a3fde5e223d733bca66a1526c3",
-                          "fetch_bytes": 5972318614, "write_bytes": 235067638,
+    "cfg2_mixtral_dist": {"source_sha256": "f50ed2c00a6685bcb0827e9601284b52bae65a09652442a6b08f729a97fa3f15",
+                          "fetch_bytes": 6020069243, "write_bytes": 235060250,
                           "profile": "profiles/gemm1_cfg2_mixtral_traffic_counters.md"},
 }
 
