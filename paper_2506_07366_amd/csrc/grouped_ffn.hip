@@ -1332,13 +1332,22 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     const int n1 = relu ? 1 : 2;            // matrices in the first product
     const int v1 = pick(g_opt_tile1.load(), n1 * fp);
     const int v2 = pick(g_opt_tile2.load(), d);
-    // N-tiles walked side by side under one run of M-tiles: all of them when the output is
-    // narrow (at most 16 tiles), else 8 (measured best on the Mixtral-shaped gate/up product)
+    // N-tiles walked side by side under one run of M-tiles.  A run of 32 tiles is 32/g M-tiles
+    // under g weight panels; every group streams the activation rows again.  Up to 12 N-tiles
+    // are walked together, so the rows are read once.  Wider outputs are walked in groups: of 4
+    // while the rows stay in the memory-side cache (8 M-tiles share each weight panel), else of
+    // 6, the near-square patch that fetches the fewest panels per run; 13 to 16 N-tiles over
+    // more than 1 GiB of rows are walked in two groups of 8.  Measured: Mixtral-shaped gate/up
+    // at 64 MiB of rows, 4 is 3-4 % faster than 8; at 512 MiB, 6 is 1 % faster than 8 and 4 is
+    // 1.5 % slower; down products of 16 N-tiles, 6 is 2-8 % faster than 16 below 1 GiB of rows,
+    // 8 is 2 % faster than 6 at 1.9 GiB.
     const int group_opt = g_opt_group_n.load();
-    auto group_for = [&](int n_cols, int bn) {
+    auto group_for = [&](int n_cols, int bn, int64_t a_bytes) {
         if (group_opt > 0) return group_opt;
         const int n_ntiles = ceil_div(n_cols, bn);
-        return n_ntiles <= 16 ? n_ntiles : 8;
+        if (n_ntiles <= 12) return n_ntiles;
+        if (n_ntiles <= 16) return a_bytes <= ((int64_t)1 << 30) ? 6 : 8;
+        return a_bytes <= ((int64_t)96 << 20) ? 4 : 6;
     };
     const GemmVariant& g1 = relu ? kGemmRelu[v1] : kGemmSwiglu[v1];
     const GemmVariant& g2 = kGemmPlain[v2];
@@ -1358,12 +1367,12 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     const bf16_t* p2 = p13 + (size_t)n1 * E * d * fp;
     if (timed) (void)hipEventRecord(g_time_events[0], st);
     rc = launch_gemm_bf16(g1, (const bf16_t*)x_in, d, p13, (size_t)n1 * d * fp, (bf16_t*)ws.h, fp, ws.tiles1,
-                          ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn), rm1, nullptr, st);
+                          ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn, A * (int64_t)d * 2), rm1, nullptr, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
     rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, fp, p2, (size_t)d * fp, (bf16_t*)y_perm, d, tiles2, count2,
-                          ws.queues + 8, d, fp, group_for(d, g2.bn), rm2, ws.partials, st);
+                          ws.queues + 8, d, fp, group_for(d, g2.bn, A * (int64_t)fp * 2), rm2, ws.partials, st);
     if (rc == MOE_OK && split) {
         hipLaunchKernelGGL(add_partials_kernel, dim3(ws.split_capacity < 64 ? ws.split_capacity : 64, 32), dim3(256),
                            0, st, ws.partials, ws.splits, count2, ws.parts, (bf16_t*)y_perm, d, d, rm2);
