@@ -21,8 +21,8 @@ inline int check_launch() {
 }
 
 // a >= 0, b > 0; no intermediate sum, so a may be as large as the type allows
-inline int ceil_div(int a, int b) { return a / b + (a % b != 0 ? 1 : 0); }
-inline int64_t ceil_div64(int64_t a, int64_t b) { return a / b + (a % b != 0 ? 1 : 0); }
+__host__ __device__ inline int ceil_div(int a, int b) { return a / b + (a % b != 0 ? 1 : 0); }
+__host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return a / b + (a % b != 0 ? 1 : 0); }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 inline int dtype_size(int dtype) { return dtype == MOE_DTYPE_BF16 ? 2 : 4; }

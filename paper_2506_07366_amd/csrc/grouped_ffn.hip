@@ -138,17 +138,18 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
                                                              int seg_end, int E, TableSpec t1, TableSpec t2,
                                                              int32_t* __restrict__ rowlist,
                                                              int32_t* __restrict__ queues, int n_queues) {
-    __shared__ int s_rows[MOE_MAX_SEGMENTS];       // rows of the segment (0: not live)
-    __shared__ int s_ex[MOE_MAX_SEGMENTS];         // its expert
+    __shared__ __align__(16) int s_rows[MOE_MAX_SEGMENTS];  // rows of the segment (0: not live)
+    __shared__ __align__(16) int s_ex[MOE_MAX_SEGMENTS];    // its expert
     __shared__ int s_first[MOE_MAX_SEGMENTS];      // first row of x_perm
     __shared__ int srt_base[MOE_MAX_SEGMENTS + 1]; // list position of the j-th segment in list order
     __shared__ int srt_first[MOE_MAX_SEGMENTS];    // its first row of x_perm
     __shared__ int e_rows[MOE_MAX_EXPERTS + 1];    // rows per expert -> list base per expert
-    __shared__ int e_segs[MOE_MAX_EXPERTS + 1];    // live segments per expert -> base in list order
+    __shared__ int e_segs[MOE_MAX_EXPERTS + 1];    // live segments per expert -> base in list order; later: whole
+                                                   //   ragged tiles of the experts below
     __shared__ int e_full[MOE_MAX_EXPERTS + 1];    // full-height tiles per expert -> base
-    __shared__ int e_tail[MOE_MAX_EXPERTS];        // rows of the expert's ragged tile
+    __shared__ __align__(16) int e_tail[MOE_MAX_EXPERTS];  // rows of the expert's ragged tile
     __shared__ int e_rank[MOE_MAX_EXPERTS];        // its place among the ragged tiles, tallest first
-    __shared__ int wave_sum[16];
+    __shared__ int wave_sum[32];
     __shared__ int total_tail, tail_rows;
     const int tid = threadIdx.x;
     const int ns = seg_end - seg_begin;
@@ -171,22 +172,64 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
         }
     }
     __syncthreads();
-    block_exclusive_scan_2048(e_rows, E, wave_sum);  // e_rows[e] = list base, e_rows[E] = rows in the range
-    block_exclusive_scan_2048(e_segs, E, wave_sum);
+    // e_rows[e] = list base, e_rows[E] = rows in the range; e_segs[e] = base in list order
+    block_exclusive_scan2_2048(e_rows, e_segs, E, wave_sum);
     const int n_list = e_rows[E], n_live = e_segs[E];
     // place of every live segment in list order: behind the segments of lower experts and the
-    // lower segments of its own expert
-    for (int i = tid; i < ns; i += blockDim.x) {
-        if (s_rows[i] == 0) continue;
-        const int e = s_ex[i];
-        int before = 0, rows_before = 0;
-        for (int j = 0; j < i; ++j)
-            if (s_rows[j] > 0 && s_ex[j] == e) {
-                ++before;
-                rows_before += s_rows[j];
+    // lower segments of its own expert.  A thread's time goes by the instructions it runs one
+    // after the other, so the pairs (segment, lower segment) are dealt over the whole workgroup:
+    // `share` threads split the lower segments of one segment between them and add their
+    // counts up in LDS (srt_base / srt_first hold them by segment until the places are known).
+    for (int i = tid; i < ns; i += blockDim.x) srt_base[i] = srt_first[i] = 0;
+    __syncthreads();
+    {
+        int width = kWave;  // threads side by side on different segments
+        while (width < ns && width < (int)blockDim.x) width <<= 1;
+        const int share = blockDim.x / width, part = tid / width;
+        const int per = ceil_div(ceil_div(ns, 4), share);  // groups of four lower segments per thread
+        for (int i = tid % width; i < ns; i += width) {
+            if (s_rows[i] == 0) continue;
+            const int e = s_ex[i];
+            int before = 0, rows_before = 0;
+            const int g_end = (part + 1) * per < ceil_div(i, 4) ? (part + 1) * per : ceil_div(i, 4);
+            for (int g = part * per; g < g_end; ++g) {  // four segments per LDS read, no branches
+                const int j0 = 4 * g;
+                const int4 r4 = *reinterpret_cast<const int4*>(&s_rows[j0]);
+                const int4 x4 = *reinterpret_cast<const int4*>(&s_ex[j0]);
+                const int rs[4] = {r4.x, r4.y, r4.z, r4.w};
+                const int xs[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool same = j0 + u < i && rs[u] > 0 && xs[u] == e;
+                    before += same ? 1 : 0;
+                    rows_before += same ? rs[u] : 0;
+                }
             }
-        srt_base[e_segs[e] + before] = e_rows[e] + rows_before;
-        srt_first[e_segs[e] + before] = s_first[i];
+            if (before) {
+                atomicAdd(&srt_base[i], before);
+                atomicAdd(&srt_first[i], rows_before);
+            }
+        }
+    }
+    __syncthreads();
+    {
+        constexpr int kPer = MOE_MAX_SEGMENTS / 1024;  // segments per thread
+        int before[kPer], rows_before[kPer];
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int i = tid + q * (int)blockDim.x;
+            before[q] = i < ns ? srt_base[i] : 0;
+            rows_before[q] = i < ns ? srt_first[i] : 0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int i = tid + q * (int)blockDim.x;
+            if (i >= ns || s_rows[i] == 0) continue;
+            const int e = s_ex[i];
+            srt_base[e_segs[e] + before[q]] = e_rows[e] + rows_before[q];
+            srt_first[e_segs[e] + before[q]] = s_first[i];
+        }
     }
     if (tid == 0) srt_base[n_live] = n_list;
     __syncthreads();
@@ -212,13 +255,18 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
         __syncthreads();
         if (tid == 0) total_tail = tail_rows = 0;
         __syncthreads();
-        for (int e = tid; e < E; e += blockDim.x) {
-            const int rows = e_rows[e + 1] - e_rows[e];
-            e_full[e] = rows / BM;
-            e_tail[e] = rows % BM;
-            if (e_tail[e]) {
-                atomicAdd(&total_tail, 1);
-                atomicAdd(&tail_rows, e_tail[e]);
+        {   // (E <= blockDim.x: one expert per thread; one LDS atomic per wavefront)
+            const int e = tid;
+            const int rows = e < E ? e_rows[e + 1] - e_rows[e] : 0;
+            const int tl = rows % BM;
+            if (e < E) {
+                e_full[e] = rows / BM;
+                e_tail[e] = tl;
+            }
+            const int n_t = wave_sum_i32(tl > 0 ? 1 : 0), r_t = wave_sum_i32(tl);
+            if ((tid & (kWave - 1)) == 0 && n_t) {
+                atomicAdd(&total_tail, n_t);
+                atomicAdd(&tail_rows, r_t);
             }
         }
         __syncthreads();
@@ -242,23 +290,49 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
         __syncthreads();
         if (tid == 0) tail_rows = 0;
         __syncthreads();
-        for (int e = tid; e < E; e += blockDim.x) {
-            const int tl = e_tail[e];
-            int rank = 0;
-            long long behind = 0;
+        // (pairs of experts dealt over the workgroup like the pairs of segments above; the
+        // half-rows behind a ragged tile are counted in srt_first, free since the row list is
+        // written: at most E * 2 * BM, an int)
+        int* e_behind = srt_first;
+        for (int e = tid; e < E; e += blockDim.x) e_rank[e] = e_behind[e] = 0;
+        __syncthreads();
+        {
+            int width = kWave;
+            while (width < E && width < (int)blockDim.x) width <<= 1;
+            const int share = blockDim.x / width, part = tid / width;
+            const int per = ceil_div(ceil_div(E, 4), share);
+            const int e = tid % width;
+            const int tl = e < E ? e_tail[e] : 0;
             if (tl > 0) {
-                for (int j = 0; j < E; ++j) {
-                    const int tj = e_tail[j];
-                    if (tj == 0) continue;
-                    if (tj > tl || (tj == tl && j < e)) ++rank;
-                    else if (j != e) behind += BM + tj;
+                int rank = 0, behind = 0;
+                const int g_end = (part + 1) * per < ceil_div(E, 4) ? (part + 1) * per : ceil_div(E, 4);
+                for (int g = part * per; g < g_end; ++g) {
+                    const int j0 = 4 * g;
+                    const int4 t4 = *reinterpret_cast<const int4*>(&e_tail[j0]);
+                    const int ts4[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u, tj = ts4[u];
+                        const bool live = j < E && tj > 0;
+                        const bool ahead = tj > tl || (tj == tl && j < e);
+                        rank += (live && ahead) ? 1 : 0;
+                        behind += (live && !ahead && j != e) ? BM + tj : 0;
+                    }
                 }
-                if (behind < want) {
-                    atomicAdd(&total_tail, 1);
-                    atomicAdd(&tail_rows, BM + tl);
-                }
+                if (rank) atomicAdd(&e_rank[e], rank);
+                if (behind) atomicAdd(&e_behind[e], behind);
             }
-            e_rank[e] = rank;
+        }
+        __syncthreads();
+        {
+            const int e = tid;
+            const int tl = e < E ? e_tail[e] : 0;
+            const bool cut = tl > 0 && (long long)e_behind[e] < want;
+            const int n_c = wave_sum_i32(cut ? 1 : 0), r_c = wave_sum_i32(cut ? BM + tl : 0);
+            if ((tid & (kWave - 1)) == 0 && n_c) {
+                atomicAdd(&total_tail, n_c);
+                atomicAdd(&tail_rows, r_c);
+            }
         }
         __syncthreads();
         n_rsplit = total_tail;
@@ -300,11 +374,10 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(const int32_t* __res
             ts.splits[split_index].rows = rows;
         };
         // whole ragged tiles of the experts below e (each sits right behind its expert's full tiles)
-        auto whole_tails_below = [&](int e) {
-            int n = 0;
-            for (int j = 0; j < e; ++j) n += (e_tail[j] > 0 && e_rank[j] < n_whole_tail) ? 1 : 0;
-            return n;
-        };
+        for (int e = tid; e < E; e += blockDim.x) e_segs[e] = (e_tail[e] > 0 && e_rank[e] < n_whole_tail) ? 1 : 0;
+        __syncthreads();
+        block_exclusive_scan_2048(e_segs, E, wave_sum);
+        auto whole_tails_below = [&](int e) { return e_segs[e]; };
         if (fits) {
             // full-height tiles: tile t belongs to the expert whose range of tile numbers holds it
             for (int t = tid; t < n_full; t += blockDim.x) {

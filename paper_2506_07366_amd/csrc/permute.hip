@@ -15,6 +15,9 @@
 //   scan2    : chunk bases per segment, seg_offsets, rank_load
 //   place    : row_of_assign / assign_of_row
 //   scatter  : each token row is read once and written to its k rows of x_perm
+//
+// A batch of at most 8192 assignments (decode, short prefill) takes the five index steps in
+// one workgroup and one launch: the same ranks and scans, the chunk being the whole batch.
 #include "common.h"
 #include "block_scan.h"
 #include <mutex>
@@ -65,15 +68,17 @@ __device__ __forceinline__ int home_slot_of(int e, int H, int S) { return (e / H
 // Stable rank of every element of a chunk among equal keys earlier in the chunk.
 // Wavefront w owns elements [w*512, (w+1)*512) of the chunk in kRounds rounds of
 // 64; element p of the chunk is (w, r, lane) with p = w*512 + r*64 + lane.
-// wcnt is LDS scratch of kPermWaves*nkeys ints.  On return rank[r] holds the
-// rank, and (if chunk_hist) chunk_hist[key] the chunk's count per key.
+// The workgroup has NWAVES wavefronts; wcnt is LDS scratch of NWAVES*nkeys ints.
+// On return rank[r] holds the rank, and (if chunk_hist) chunk_hist[key] the chunk's
+// count per key.  Only the first `rounds` rounds hold elements (uniform over the workgroup).
 // ---------------------------------------------------------------------------
+template <int NWAVES>
 __device__ void chunk_stable_rank(const int (&key)[kRounds], const bool (&valid)[kRounds], int nkeys, int* wcnt,
-                                  int (&rank)[kRounds], int32_t* chunk_hist) {
+                                  int (&rank)[kRounds], int32_t* chunk_hist, int rounds = kRounds) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = tid / kWave;
-    for (int i = tid; i < kPermWaves * nkeys; i += kPermThreads) wcnt[i] = 0;
+    for (int i = tid; i < NWAVES * nkeys; i += NWAVES * kWave) wcnt[i] = 0;
     __syncthreads();
     int nbits = 1;
     while ((1 << nbits) < nkeys) ++nbits;
@@ -81,6 +86,8 @@ __device__ void chunk_stable_rank(const int (&key)[kRounds], const bool (&valid)
     int* mine = wcnt + w * nkeys;
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
+        rank[r] = 0;
+        if (r >= rounds) continue;
         // lanes of this round holding the same key
         unsigned long long same = __ballot(valid[r]);
         for (int b = 0; b < nbits; ++b) {
@@ -88,7 +95,6 @@ __device__ void chunk_stable_rank(const int (&key)[kRounds], const bool (&valid)
             const unsigned long long m = __ballot(valid[r] && bit);
             same &= bit ? m : ~m;
         }
-        rank[r] = 0;
         if (valid[r]) {
             const int prior = mine[key[r]];
             rank[r] = prior + __popcll(same & lt);
@@ -97,20 +103,22 @@ __device__ void chunk_stable_rank(const int (&key)[kRounds], const bool (&valid)
     }
     __syncthreads();
     // exclusive prefix over the wavefronts, per key
-    for (int kk = tid; kk < nkeys; kk += kPermThreads) {
+    for (int kk = tid; kk < nkeys; kk += NWAVES * kWave) {
+        int c[NWAVES];  // all reads, then all writes: the reads overlap
+#pragma unroll
+        for (int ww = 0; ww < NWAVES; ++ww) c[ww] = wcnt[ww * nkeys + kk];
         int run = 0;
 #pragma unroll
-        for (int ww = 0; ww < kPermWaves; ++ww) {
-            const int c = wcnt[ww * nkeys + kk];
+        for (int ww = 0; ww < NWAVES; ++ww) {
             wcnt[ww * nkeys + kk] = run;
-            run += c;
+            run += c[ww];
         }
         if (chunk_hist) chunk_hist[kk] = run;
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kRounds; ++r)
-        if (valid[r]) rank[r] += mine[key[r]];
+        if (r < rounds && valid[r]) rank[r] += mine[key[r]];
 }
 
 // ---------------------------------------------------------------------------
@@ -176,6 +184,43 @@ __device__ __forceinline__ void wave_columns_scan(int32_t* table, int nb, int nc
     for (int i = 0; i < NC; ++i) total[i] = carry[i];
 }
 
+// Replicas of expert e in ascending slot id with the exclusive upper bound of each
+// replica's range of ranks, by one wavefront (every lane active).
+__device__ __forceinline__ void replica_table(int e, int mode, int G, int nseg, const int32_t* __restrict__ hist_true,
+                                              const int32_t* __restrict__ hist_pred,
+                                              const int32_t* __restrict__ slot_expert,
+                                              const int32_t* __restrict__ slot_quota, const PermWs& ws) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    long long n_true = 0, n_hat = 0;
+    if (mode == MOE_MODE_DISTRIBUTION) {
+        n_true = hist_true[e];
+        n_hat = hist_pred[e];
+    }
+    int cnt = 0;
+    long long cum = 0;
+    if (!(mode == MOE_MODE_DISTRIBUTION && n_hat <= 0)) {
+        for (int s0 = 0; s0 < nseg; s0 += kWave) {
+            const int sigma = s0 + lane;
+            const bool match = sigma < nseg && slot_expert[sigma] == e;
+            const long long qv = match ? (long long)slot_quota[sigma] : 0ll;
+            const long long incl = wave_incl_scan(qv);
+            const unsigned long long m = __ballot(match);
+            const int pos = cnt + __popcll(m & lt);
+            if (match && pos < G) {
+                long long hi = cum + incl;                                       // Q_{r+1}
+                if (mode == MOE_MODE_DISTRIBUTION) hi = (n_true * hi) / n_hat;   // floor(n_e * Q / nhat_e)
+                if (hi > 0x7fffffffLL) hi = 0x7fffffffLL;
+                ws.rep_slot[(size_t)e * G + pos] = sigma;
+                ws.rep_hi[(size_t)e * G + pos] = (int)hi;
+            }
+            cnt += __popcll(m);
+            cum += __shfl(incl, kWave - 1, kWave);
+        }
+    }
+    if (lane == 0) ws.rep_cnt[e] = cnt < G ? cnt : G;
+}
+
 // chunk bases per expert (in place) and the replica tables of the plan; one
 // wavefront per expert column, columns dealt over the whole grid
 constexpr int kScan1Threads = 256;
@@ -185,41 +230,26 @@ __global__ __launch_bounds__(kScan1Threads) void perm_scan1_kernel(int mode, int
                                                            const int32_t* __restrict__ slot_expert,
                                                            const int32_t* __restrict__ slot_quota, PermWs ws) {
     const int nseg = G * S;
-    const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
-    const unsigned long long lt = (1ull << lane) - 1ull;
     for (int e = blockIdx.x * nwaves + wave; e < E; e += gridDim.x * nwaves) {
         int unused[1];
         wave_columns_scan<1>(ws.bh1, nb, E, e, unused);
-        // replicas of e in ascending slot id with the upper bound of their range
-        long long n_true = 0, n_hat = 0;
-        if (mode == MOE_MODE_DISTRIBUTION) {
-            n_true = hist_true[e];
-            n_hat = hist_pred[e];
-        }
-        int cnt = 0;
-        long long cum = 0;
-        if (!(mode == MOE_MODE_DISTRIBUTION && n_hat <= 0)) {
-            for (int s0 = 0; s0 < nseg; s0 += kWave) {
-                const int sigma = s0 + lane;
-                const bool match = sigma < nseg && slot_expert[sigma] == e;
-                const long long qv = match ? (long long)slot_quota[sigma] : 0ll;
-                const long long incl = wave_incl_scan(qv);
-                const unsigned long long m = __ballot(match);
-                const int pos = cnt + __popcll(m & lt);
-                if (match && pos < G) {
-                    long long hi = cum + incl;                                       // Q_{r+1}
-                    if (mode == MOE_MODE_DISTRIBUTION) hi = (n_true * hi) / n_hat;   // floor(n_e * Q / nhat_e)
-                    if (hi > 0x7fffffffLL) hi = 0x7fffffffLL;
-                    ws.rep_slot[(size_t)e * G + pos] = sigma;
-                    ws.rep_hi[(size_t)e * G + pos] = (int)hi;
-                }
-                cnt += __popcll(m);
-                cum += __shfl(incl, kWave - 1, kWave);
-            }
-        }
-        if (lane == 0) ws.rep_cnt[e] = cnt < G ? cnt : G;
+        replica_table(e, mode, G, nseg, hist_true, hist_pred, slot_expert, slot_quota, ws);
     }
+}
+
+// Segment of an assignment to expert e that stands at place i of the plan's order for e
+// (i < 0: the assignment is outside the plan's order and goes to the home slot).
+__device__ __forceinline__ int segment_of(int e, int i, int H, int S, int G, const PermWs& ws) {
+    int sg = home_slot_of(e, H, S);
+    if (i < 0) return sg;
+    const int cnt = ws.rep_cnt[e];
+    if (cnt > 0) {
+        int rr = 0;
+        while (rr < cnt - 1 && i >= ws.rep_hi[(size_t)e * G + rr]) ++rr;
+        sg = ws.rep_slot[(size_t)e * G + rr];
+    }
+    return sg;
 }
 
 // segment id per assignment + per-chunk segment histogram
@@ -253,7 +283,7 @@ __global__ __launch_bounds__(kPermThreads) void perm_segment_kernel(int mode, in
         rank[r] = 0;
     }
     if (mode != MOE_MODE_NONE) {
-        chunk_stable_rank(key, valid, E, wcnt, rank, nullptr);
+        chunk_stable_rank<kPermWaves>(key, valid, E, wcnt, rank, nullptr);
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
             const int p = w * (kRounds * kWave) + r * kWave + lane;
@@ -279,13 +309,7 @@ __global__ __launch_bounds__(kPermThreads) void perm_segment_kernel(int mode, in
                 }
             }
         }
-        int sg = home_slot_of(e, H, S);
-        const int cnt = ws.rep_cnt[e];
-        if (i >= 0 && cnt > 0) {
-            int rr = 0;
-            while (rr < cnt - 1 && i >= ws.rep_hi[(size_t)e * G + rr]) ++rr;
-            sg = ws.rep_slot[(size_t)e * G + rr];
-        }
+        const int sg = segment_of(e, i, H, S, G, ws);
         ws.seg[base + p] = sg;
         atomicAdd(&seg_bins[sg], 1);
     }
@@ -340,7 +364,7 @@ __global__ __launch_bounds__(kPermThreads) void perm_place_kernel(int T, int k, 
         valid[r] = p < n_b;
         key[r] = valid[r] ? ws.seg[base + p] : 0;
     }
-    chunk_stable_rank(key, valid, nseg, wcnt, rank, nullptr);
+    chunk_stable_rank<kPermWaves>(key, valid, nseg, wcnt, rank, nullptr);
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = w * (kRounds * kWave) + r * kWave + lane;
@@ -348,6 +372,225 @@ __global__ __launch_bounds__(kPermThreads) void perm_place_kernel(int T, int k, 
         const int row = seg_offsets[key[r]] + ws.bh2[(size_t)blockIdx.x * nseg + key[r]] + rank[r];
         row_of_assign[base + p] = row;
         assign_of_row[row] = (int)(base + p);
+    }
+}
+
+// All five index steps for a batch of at most kSmallA assignments, E and G*S at most
+// kSmallKeys, in one workgroup of 1024 threads: the chunk is the whole batch, so the chunk
+// bases are zero and both scans run in LDS.  A thread's time here goes by the number of
+// instructions it runs one after the other, so the batch is dealt over all 16 wavefronts in
+// as few rounds of 64 as hold it.  The replica tables live in LDS, one entry per slot: the
+// upper bound of the slot's range of ranks and the next slot of the same expert (ascending
+// slot id), plus every expert's first slot.  Same ranks, same results as the kernels above.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallWaves = kSmallThreads / kWave;
+constexpr int kSmallA = kSmallThreads * kRounds;  // 8192
+constexpr int kSmallKeys = 512;
+
+// The per-slot tables, by one wavefront, 64 slots at a time in ascending order: the lanes
+// holding one expert find each other by ballots; what earlier chunks hold for the expert
+// (slots, quota, last slot) is carried in LDS.
+struct SmallTables {
+    int* s_e;         // [kSmallKeys] expert of the slot (-1 beyond the plan's slots)
+    int* s_q;         // [kSmallKeys] its quota
+    long long* s_cum; // [kSmallKeys] quota of the expert's slots up to and including this one
+    int* s_next;      // [kSmallKeys] next slot of the same expert, -1: none
+    int* e_first;     // [kSmallKeys] first slot of the expert, -1: home slot only
+    int* e_cnt;       // [kSmallKeys] slots of the expert so far
+    int* e_last;      // [kSmallKeys] the last of them
+    long long* e_cum; // [kSmallKeys] their quota
+};
+__device__ __forceinline__ void small_slot_tables(int E, int nseg, const SmallTables& t) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const unsigned long long bit = 1ull << lane;
+    const unsigned long long lt = bit - 1ull;
+    int nbits = 1;
+    while ((1 << nbits) < E) ++nbits;
+    for (int s0 = 0; s0 < nseg; s0 += kWave) {
+        const int sigma = s0 + lane;
+        const int e = sigma < nseg ? t.s_e[sigma] : -1;
+        const bool ok = e >= 0 && e < E;
+        const int q = ok ? t.s_q[sigma] : 0;
+        unsigned long long same = __ballot(ok);
+        for (int b = 0; b < nbits; ++b) {
+            const bool one = (e >> b) & 1;
+            const unsigned long long m = __ballot(ok && one);
+            same &= one ? m : ~m;
+        }
+        if (!ok) same = 0ull;
+        // quota of the expert's slots of this chunk up to this one: lanes take the set bits of
+        // their mask one by one, as many steps as the largest group of the chunk has lanes
+        long long cum = 0;
+        unsigned long long todo = same & (lt | bit);
+        while (__any(todo != 0ull)) {
+            const int src = todo ? __ffsll((long long)todo) - 1 : lane;
+            const int qs = __shfl(q, src, kWave);
+            cum += todo ? (long long)qs : 0ll;
+            todo &= todo - 1ull;
+        }
+        if (ok) {
+            const int prior = t.e_cnt[e];
+            const int last = t.e_last[e];
+            cum += t.e_cum[e];
+            const unsigned long long above = same & ~(lt | bit);
+            t.s_cum[sigma] = cum;
+            t.s_next[sigma] = above ? s0 + __ffsll((long long)above) - 1 : -1;
+            if ((same & lt) == 0ull) {  // first lane of the expert in this chunk
+                if (prior == 0) t.e_first[e] = sigma;
+                else t.s_next[last] = sigma;
+            }
+            if (above == 0ull) {        // last lane: hand the totals on
+                t.e_cnt[e] = prior + __popcll(same);
+                t.e_cum[e] = cum;
+                t.e_last[e] = sigma;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kSmallThreads) void perm_small_kernel(
+    int mode, int T, int k, int E, int G, int S, const int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ pred_idx, const int32_t* __restrict__ hist_true, const int32_t* __restrict__ hist_pred,
+    const int32_t* __restrict__ slot_expert, const int32_t* __restrict__ slot_quota,
+    int32_t* __restrict__ seg_offsets, int32_t* __restrict__ row_of_assign, int32_t* __restrict__ assign_of_row,
+    int32_t* __restrict__ rank_load) {
+    // one buffer, three lives: wavefront counters of the first rank; rank and key by position
+    // (token-to-expert mode looks up those of the token's predicted ids); counters of the second
+    __shared__ int buf[kSmallWaves * kSmallKeys];
+    static_assert(kSmallWaves * kSmallKeys >= kSmallA, "ranks by position share the counters' buffer");
+    static_assert(kSmallA <= (1 << 16) && kSmallKeys <= (1 << 15), "rank and key share one int");
+    __shared__ int s_e[kSmallKeys], s_q[kSmallKeys], s_hi[kSmallKeys], s_next[kSmallKeys];
+    __shared__ int e_first[kSmallKeys], e_cnt[kSmallKeys], e_last[kSmallKeys], e_true[kSmallKeys], e_hat[kSmallKeys];
+    __shared__ int e_home[kSmallKeys];  // home slot of the expert
+    __shared__ long long e_cum[kSmallKeys], s_cum[kSmallKeys];
+    __shared__ int tot[kSmallKeys + 1];
+    __shared__ int wave_sum[16];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = tid / kWave;
+    const int nseg = G * S;
+    const int H = (E + G - 1) / G;
+    const int n_b = T * k;
+    // rounds of 64 per wavefront that hold the batch; element p is (w, r, lane) with
+    // p = (w * rounds + r) * 64 + lane
+    const int rounds = (n_b + kSmallThreads - 1) / kSmallThreads;
+
+    int key[kRounds], rank[kRounds], expert[kRounds];
+    bool valid[kRounds];
+    const int32_t* rank_keys = (mode == MOE_MODE_TOKEN) ? pred_idx : topk_idx;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = (w * rounds + r) * kWave + lane;
+        valid[r] = r < rounds && p < n_b;
+        key[r] = valid[r] ? clamp_key(rank_keys[p], E) : 0;
+        expert[r] = key[r];
+        rank[r] = 0;
+    }
+    if (mode == MOE_MODE_TOKEN) {
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const int p = (w * rounds + r) * kWave + lane;
+            if (valid[r]) expert[r] = clamp_key(topk_idx[p], E);
+        }
+    }
+    for (int e = tid; e < E; e += kSmallThreads) e_home[e] = home_slot_of(e, H, S);
+    if (mode != MOE_MODE_NONE) {
+        for (int i = tid; i < kSmallKeys; i += kSmallThreads) {
+            s_e[i] = i < nseg ? slot_expert[i] : -1;
+            s_q[i] = i < nseg ? slot_quota[i] : 0;
+            e_first[i] = e_last[i] = -1;
+            e_cnt[i] = 0;
+            e_cum[i] = 0ll;
+            if (mode == MOE_MODE_DISTRIBUTION && i < E) {
+                e_true[i] = hist_true[i];
+                e_hat[i] = hist_pred[i];
+            }
+        }
+        __syncthreads();
+        if (w == kSmallWaves - 1) {
+            const SmallTables t{s_e, s_q, s_cum, s_next, e_first, e_cnt, e_last, e_cum};
+            small_slot_tables(E, nseg, t);
+        }
+        chunk_stable_rank<kSmallWaves>(key, valid, E, buf, rank, nullptr, rounds);
+        __syncthreads();  // the counters are dead, the buffer becomes rank and key by position
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const int p = (w * rounds + r) * kWave + lane;
+            if (valid[r]) buf[p] = rank[r] | (key[r] << 16);
+        }
+        // upper bound of every slot's range of ranks from the quota up to it, all slots at once
+        if (tid < nseg) {
+            const int e = s_e[tid];
+            long long hi = s_cum[tid];                                                  // Q_{r+1}
+            if (mode == MOE_MODE_DISTRIBUTION && e >= 0 && e < E && e_hat[e] > 0)
+                hi = ((long long)e_true[e] * hi) / e_hat[e];                            // floor(n_e * Q / nhat_e)
+            if (hi > 0x7fffffffLL) hi = 0x7fffffffLL;
+            s_hi[tid] = (int)hi;
+        }
+        // an expert nobody is predicted for keeps its home slot
+        if (mode == MOE_MODE_DISTRIBUTION && tid < E && e_hat[tid] <= 0) e_first[tid] = -1;
+    }
+    __syncthreads();
+
+    // segment of every assignment: its place i in the plan's order for its expert (-1: none),
+    // then a walk over the expert's slots, at most G of them, to the one whose range holds i;
+    // the rounds walk in step so that their LDS reads overlap
+    int sg[kRounds], place[kRounds];
+    bool walking[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = (w * rounds + r) * kWave + lane;
+        sg[r] = 0;
+        place[r] = -1;
+        walking[r] = false;
+        if (!valid[r]) continue;
+        if (mode == MOE_MODE_DISTRIBUTION) {
+            place[r] = rank[r];
+        } else if (mode == MOE_MODE_TOKEN) {
+            const int row0 = (p / k) * k;  // the token's predicted ids
+            for (int jp = 0; jp < k; ++jp) {
+                const int v = buf[row0 + jp];
+                if ((v >> 16) == expert[r]) {
+                    place[r] = v & 0xffff;
+                    break;
+                }
+            }
+        }
+        sg[r] = e_home[expert[r]];
+        if (place[r] >= 0) {
+            const int first = e_first[expert[r]];
+            if (first >= 0) {
+                sg[r] = first;
+                walking[r] = true;
+            }
+        }
+    }
+    for (int seen = 1; mode != MOE_MODE_NONE && seen < G; ++seen) {
+        bool more = false;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {  // no branches: sg[r] is a slot in any case, the reads overlap
+            if (r >= rounds) continue;       // (uniform)
+            const int nx = s_next[sg[r]];
+            const int hi = s_hi[sg[r]];
+            walking[r] = walking[r] && nx >= 0 && place[r] >= hi;
+            sg[r] = walking[r] ? nx : sg[r];
+            more = more || walking[r];
+        }
+        if (!__any(more)) break;
+    }
+    __syncthreads();  // every look-up of a rank is done before the buffer holds counters again
+
+    chunk_stable_rank<kSmallWaves>(sg, valid, nseg, buf, rank, tot, rounds);
+    block_exclusive_scan_2048(tot, nseg, wave_sum);
+    for (int s = tid; s <= nseg; s += kSmallThreads) seg_offsets[s] = tot[s];
+    for (int g = tid; g < G; g += kSmallThreads) rank_load[g] = tot[(g + 1) * S] - tot[g * S];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = (w * rounds + r) * kWave + lane;
+        if (!valid[r]) continue;
+        const int row = tot[sg[r]] + rank[r];
+        row_of_assign[p] = row;
+        assign_of_row[row] = p;
     }
 }
 
@@ -423,27 +666,37 @@ static int permute_impl(int mode, const void* x, int dtype, int T, int d, int E,
     hipStream_t st = (hipStream_t)stream;
     const int nb = T > 0 ? ceil_div(T, tokens_per_chunk(k)) : 0;
     int rc;
-    if (nb > 0 && mode != MOE_MODE_NONE) {
-        const int32_t* keys = (mode == MOE_MODE_TOKEN) ? pred_idx : topk_idx;
-        hipLaunchKernelGGL(perm_count_kernel, dim3(nb), dim3(kPermThreads), 0, st, keys, T, k, E, ws.bh1);
+    const bool small = (int64_t)T * k <= kSmallA && E <= kSmallKeys && G * S <= kSmallKeys;
+    if (small) {
+        hipLaunchKernelGGL(perm_small_kernel, dim3(1), dim3(kSmallThreads), 0, st, mode, T, k, E, G, S, topk_idx,
+                           pred_idx, hist_true, hist_pred, slot_expert, slot_quota, seg_offsets, row_of_assign,
+                           assign_of_row, rank_load);
         if ((rc = check_launch()) != MOE_OK) return rc;
-    }
-    if (mode != MOE_MODE_NONE) {
-        hipLaunchKernelGGL(perm_scan1_kernel, dim3(ceil_div(E, kScan1Threads / kWave)), dim3(kScan1Threads), 0, st,
-                           mode, nb, E, G, S, hist_true, hist_pred, slot_expert, slot_quota, ws);
+    } else {
+        if (nb > 0 && mode != MOE_MODE_NONE) {
+            const int32_t* keys = (mode == MOE_MODE_TOKEN) ? pred_idx : topk_idx;
+            hipLaunchKernelGGL(perm_count_kernel, dim3(nb), dim3(kPermThreads), 0, st, keys, T, k, E, ws.bh1);
+            if ((rc = check_launch()) != MOE_OK) return rc;
+        }
+        if (mode != MOE_MODE_NONE) {
+            hipLaunchKernelGGL(perm_scan1_kernel, dim3(ceil_div(E, kScan1Threads / kWave)), dim3(kScan1Threads), 0, st,
+                               mode, nb, E, G, S, hist_true, hist_pred, slot_expert, slot_quota, ws);
+            if ((rc = check_launch()) != MOE_OK) return rc;
+        }
+        if (nb > 0) {
+            hipLaunchKernelGGL(perm_segment_kernel, dim3(nb), dim3(kPermThreads), 0, st, mode, T, k, E, G, S, topk_idx,
+                               pred_idx, ws);
+            if ((rc = check_launch()) != MOE_OK) return rc;
+        }
+        hipLaunchKernelGGL(perm_scan2_kernel, dim3(1), dim3(1024), 0, st, nb, G, S, ws, seg_offsets, rank_load);
         if ((rc = check_launch()) != MOE_OK) return rc;
+        if (nb > 0) {
+            hipLaunchKernelGGL(perm_place_kernel, dim3(nb), dim3(kPermThreads), 0, st, T, k, G, S, ws, seg_offsets,
+                               row_of_assign, assign_of_row);
+            if ((rc = check_launch()) != MOE_OK) return rc;
+        }
     }
     if (nb > 0) {
-        hipLaunchKernelGGL(perm_segment_kernel, dim3(nb), dim3(kPermThreads), 0, st, mode, T, k, E, G, S, topk_idx,
-                           pred_idx, ws);
-        if ((rc = check_launch()) != MOE_OK) return rc;
-    }
-    hipLaunchKernelGGL(perm_scan2_kernel, dim3(1), dim3(1024), 0, st, nb, G, S, ws, seg_offsets, rank_load);
-    if ((rc = check_launch()) != MOE_OK) return rc;
-    if (nb > 0) {
-        hipLaunchKernelGGL(perm_place_kernel, dim3(nb), dim3(kPermThreads), 0, st, T, k, G, S, ws, seg_offsets,
-                           row_of_assign, assign_of_row);
-        if ((rc = check_launch()) != MOE_OK) return rc;
         if (x_perm) {
             const int chunks = (int)((size_t)d * dtype_size(dtype) / 16);
             const int unroll = chunks >= 4 * kWave ? 4 : 1;

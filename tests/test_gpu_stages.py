@@ -160,7 +160,11 @@ def test_plan_many_ranks():
                                        (3000, 1000, 4, 128, 16),     # 16 slots per rank
                                        # whole numbers of 2048-assignment chunks and one over; 256 / 257 experts
                                        (4096, 8, 2, 8, 2), (8192, 8, 1, 8, 2), (8193, 8, 1, 8, 2),
-                                       (512, 256, 16, 64, 4), (512, 257, 16, 64, 5), (2731, 64, 3, 16, 5)])
+                                       (512, 256, 16, 64, 4), (512, 257, 16, 64, 5), (2731, 64, 3, 16, 5),
+                                       # both sides of the one-workgroup path's limits: 8192 assignments,
+                                       # 512 experts, 512 segments
+                                       (400, 512, 8, 64, 8), (400, 513, 8, 64, 9), (1024, 300, 8, 32, 16),
+                                       (1024, 300, 8, 33, 16), (1, 1, 1, 1, 1), (8192, 512, 1, 128, 4)])
 def test_permute_small(mode, T, E, k, G, S):
     cfg = wl.MoEConfig("p", T=T, d=16, ffn=8, E=E, k=k, G=G, S=S, dtype="f32", mode=mode, alpha=0.3,
                        sigma_pred=0.3, acc=0.8, seed=T + E)
