@@ -172,7 +172,11 @@ int moe_permute_static(int mode, const void* x, int dtype, int T, int d, int E, 
  * duplication's communication overhead"; not part of the per-batch path).
  *   W1, W3 [E, d, ffn], W2 [E, ffn, d]  dtype in (row-major)
  *   packed  out, moe_packed_weights_bytes(E, d, ffn, dtype) bytes
- * For MOE_DTYPE_F32 the packed form is a plain copy.
+ * For MOE_DTYPE_F32 the packed form is a plain copy.  For MOE_DTYPE_BF16 every matrix is
+ * stored transposed, in tiles of 256 output columns by 64 of the contracted dimension,
+ * each tile 32 KiB in one piece in the order the kernels hold it on chip; the hidden width
+ * is padded to a multiple of 64 and the output columns to whole tiles with zeros (the
+ * size query includes the padding).  The packed form is opaque: only these calls read it.
  */
 size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype);
 int moe_pack_weights(const void* W1, const void* W3, const void* W2, int dtype,

@@ -69,9 +69,28 @@ constexpr int kCntEntries = 0, kCntPass0 = 1, kCntPass1 = 2, kCntSplit = 3, kCnt
 // ---------------------------------------------------------------------------
 // weight packing (one-off, weights are static across inputs)
 // ---------------------------------------------------------------------------
-// out[n][k] = in[k][n] for one expert per blockIdx.z, zero where k >= K or n >= N (the
-// output is K_out x N_out, padded); optional interleave of the output row index: rows
-// of W1 go to (n/32)*64 + n%32, rows of W3 32 further.
+// The packed form of a weight matrix is what the GEMM's loads want to find: the transposed
+// matrix W^T [N_out][K_out] cut into tiles of kPackN rows by kPackK columns, tiles of one
+// row block side by side along K, every tile 32 KiB in one piece and laid out exactly as
+// it sits in LDS (row r, 16-byte piece c of the row at piece c ^ swz(r)).  A k-tile of a
+// weight panel is then one contiguous read instead of 256 pieces of 128 bytes a row apart,
+// which the memory system serves a quarter slower at some row lengths (8 KiB among them).
+constexpr int kPackN = 256, kPackK = 64;
+// 16-byte piece `slot` of LDS row `row` holds piece slot ^ swz(row) of the row.  The LDS
+// has 64 four-byte banks and serves a ds_read_b128 sixteen lanes at a time, so the
+// 16 consecutive rows one such group touches must land on 16 distinct 16-byte bank
+// groups of a 256-byte span: with 128-byte rows that is (row&1, slot) -> xor with
+// (row>>1)&7.
+__host__ __device__ inline int swz(int row) { return (row >> 1) & 7; }
+__host__ __device__ inline size_t packed_index(int n, int k, int K_out) {
+    const int row = n % kPackN, kk = k % kPackK;
+    const size_t tile = (size_t)(n / kPackN) * (K_out / kPackK) + k / kPackK;
+    return (tile * kPackN + row) * kPackK + (((kk >> 3) ^ swz(row)) << 3) + (kk & 7);
+}
+
+// out[packed_index(n, k)] = in[k][n] for one expert per blockIdx.z, zero where k >= K or
+// n >= N (the output is K_out x N_out, padded); optional interleave of the output row
+// index: rows of W1 go to (n/32)*64 + n%32, rows of W3 32 further.
 __global__ __launch_bounds__(256) void pack_transpose_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
                                                               int K, int N, int K_out, int N_out,
                                                               size_t in_expert_stride, size_t out_expert_stride,
@@ -90,7 +109,7 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const bf16_t* __res
         const int nn = n0 + r, kk = k0 + tx;
         if (nn < N_out && kk < K_out) {
             const int orow = interleave ? ((nn / 32) * 64 + sel * 32 + (nn % 32)) : nn;
-            dst[(size_t)orow * K_out + kk] = tile[tx][r];
+            dst[packed_index(orow, kk, K_out)] = tile[tx][r];
         }
     }
 }
@@ -491,13 +510,6 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // exponential in place of an IEEE division and expf; the result is rounded to bf16 right after.
 __device__ __forceinline__ float silu_f(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
-// 16-byte piece `slot` of LDS row `row` holds global piece slot ^ swz(row).  The LDS
-// has 64 four-byte banks and serves a ds_read_b128 sixteen lanes at a time, so the
-// 16 consecutive rows one such group touches must land on 16 distinct 16-byte bank
-// groups of a 256-byte span: with 128-byte rows that is (row&1, slot) -> xor with
-// (row>>1)&7.
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
-
 // EPI selects what happens to the accumulators before they are stored: kEpiNone (plain
 // product, optionally scaled per row), kEpiSwiglu (silu(gate) * up on interleaved column
 // pairs, half as many output columns), kEpiRelu (max(., 0)).
@@ -521,7 +533,7 @@ struct RowMap {
 template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, int lda,           // activations [rows, K]
-    const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N][K]
+    const bf16_t* __restrict__ Bp, size_t b_stride,  // packed weights [E][N-tile][k-tile][kPackN x kPackK]
     bf16_t* __restrict__ C, int ldc,                 // output [rows, SWIGLU ? N/2 : N]
     const MTile* __restrict__ mtiles, const int32_t* __restrict__ counts, int32_t* __restrict__ queues,
     int N, int K, int group_n, RowMap rm,
@@ -541,6 +553,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     static_assert(!SWIGLU || (WTN % 64 == 0), "gate/up pairs must sit in one wavefront");
     static_assert(LPT * NSTAGE < 64, "vmcnt range");
     static_assert(CPR == 8 && BK == 64 && TM16 + TN16 <= 12, "the K loop is written for 64-deep k-tiles");
+    static_assert(BN == kPackN && BK == kPackK, "a weight tile is one tile of the packed form");
     // With two stages every wait drains all loads, so loads of rows past the end of a
     // ragged M-tile can simply be left out; with deeper prefetch the wait counts a fixed
     // number of loads per k-tile and such rows are clamped to the last valid row instead.
@@ -656,13 +669,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // rows that go through a list are addressed from the start of A (32-bit byte offsets:
         // the host checks that A fits), rows in place from the tile's first row
         const bf16_t* Ab = (rm.a_rows ? A : A + (size_t)mt.list0 * lda) + mt.kt0 * BK;
-        const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + (size_t)n0 * K + mt.kt0 * BK;
+        const bf16_t* Bb = Bp + (size_t)mt.expert * b_stride + ((size_t)nt_i * (K / BK) + mt.kt0) * (BN * BK);
         const int n_valid = (N - n0) < BN ? (N - n0) : BN;
 
-        // per-lane byte offsets of the pieces this lane fetches (rows beyond the segment /
-        // matrix edge are clamped to the last valid row; their products are computed and
-        // dropped in the epilogue).  (uniform base) + (32-bit lane offset) is an addressing
-        // mode of the load instruction, so the loads spend no vector ALU work on addresses.
+        // per-lane byte offsets of the pieces this lane fetches (activation rows beyond the
+        // segment are clamped to the last valid row, weight rows beyond the matrix edge are
+        // zero rows of the packed form; their products are computed and dropped in the
+        // epilogue).  (uniform base) + (32-bit lane offset) is an addressing mode of the load
+        // instruction, so the loads spend no vector ALU work on addresses.  A weight tile is
+        // stored as it sits in LDS: load i of the wavefront takes its 1 KiB of it as it comes.
         unsigned offA_b[IAW], offB_b[IBW];
         const int lane_p = opaque(lane);
 #pragma unroll
@@ -677,12 +692,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             offA_b[i] = ((unsigned)r * (unsigned)lda + (unsigned)((slot ^ swz(row)) * 8)) * 2u;
         }
 #pragma unroll
-        for (int i = 0; i < IBW; ++i) {
-            const int p = (wave + i * NW) * 64 + lane_p;
-            const int row = p / CPR, slot = p % CPR;
-            const int r = row < n_valid ? row : n_valid - 1;
-            offB_b[i] = ((unsigned)r * (unsigned)K + (unsigned)((slot ^ swz(row)) * 8)) * 2u;
-        }
+        for (int i = 0; i < IBW; ++i) offB_b[i] = (unsigned)(((wave + i * NW) * 64 + lane_p) * 16);
 
         // load l of this wavefront's LPT loads of k-tile kt (activations first), one instruction
         const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -695,7 +705,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                 if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
                     global_to_lds_b128(base, offA_b[l], sA + (unsigned)(l * NW * 1024));
             } else {
-                const unsigned char* base = (const unsigned char*)Bb + (size_t)(kt * (BK * 2));
+                const unsigned char* base = (const unsigned char*)Bb + (size_t)kt * B_BYTES;
                 global_to_lds_b128(base, offB_b[l - IAW], sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
             }
         };
@@ -1106,6 +1116,11 @@ static inline bool ffn_shape_in_range(int64_t A, int d, int ffn, int nseg, int d
 static inline int padded_ffn(int ffn, int dtype) {
     return dtype == MOE_DTYPE_BF16 ? (int)align_up((size_t)ffn, 64) : ffn;
 }
+// rows of a packed bf16 weight matrix: whole tiles
+static inline size_t packed_rows(size_t n) { return align_up(n, (size_t)kPackN); }
+// elements of one expert's packed matrices: the first product's n1 matrices, the second product's
+static inline size_t packed_elems1(int n1, int d, int fp) { return packed_rows((size_t)n1 * fp) * d; }
+static inline size_t packed_elems2(int d, int fp) { return packed_rows((size_t)d) * fp; }
 
 // Whether (and how) the closing tiles of the second product are computed as parts of K.  It
 // pays when the product has only a few rounds of tiles per workgroup, so that the uneven end
@@ -1259,8 +1274,11 @@ extern "C" int moe_grouped_ffn_set_option(int option, int value) {
 }
 
 extern "C" size_t moe_packed_weights_bytes(int E, int d, int ffn, int dtype) {
-    if (E < 1 || E > MOE_MAX_EXPERTS || !moegps::ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
-    return (size_t)3 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
+    using namespace moegps;
+    if (E < 1 || E > MOE_MAX_EXPERTS || !ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
+    if (dtype != MOE_DTYPE_BF16) return (size_t)3 * E * d * ffn * dtype_size(dtype);
+    const int fp = padded_ffn(ffn, dtype);
+    return (size_t)E * (packed_elems1(2, d, fp) + packed_elems2(d, fp)) * sizeof(bf16_t);
 }
 
 namespace moegps {
@@ -1288,24 +1306,27 @@ static int pack_weights_impl(const void* W1, const void* W3, const void* W2, int
     const int fp = padded_ffn(ffn, dtype);
     const int n1 = W3 ? 2 : 1;              // matrices in the first product
     const size_t es = (size_t)d * ffn;      // one expert's matrix as given
-    const size_t ep = (size_t)d * fp;       // and padded
-    bf16_t* p1 = (bf16_t*)packed;           // [E][n1*fp][d]; gate/up interleaved by 32 columns when n1 = 2
-    bf16_t* p2 = p1 + n1 * E * ep;          // [E][d][fp]
-    // W1 (, W3): in[k = d][n = ffn] -> out[n'][d], zero rows for n >= ffn
-    dim3 g13(fp / 32, d / 32, E);
-    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p1, d, ffn, d, fp, es,
-                       n1 * ep, W3 ? 1 : 0, 0);
+    const size_t e1 = packed_elems1(n1, d, fp), e2 = packed_elems2(d, fp);  // and packed
+    bf16_t* p1 = (bf16_t*)packed;           // [E] packed [n1*fp][d]; gate/up interleaved by 32 columns when n1 = 2
+    bf16_t* p2 = p1 + (size_t)E * e1;       // [E] packed [d][fp]
+    // W1 (, W3): in[k = d][n = ffn] -> rows n' of the packed matrix, zero rows for n >= ffn and up
+    // to whole tiles of rows
+    const int rows1 = (int)(packed_rows((size_t)n1 * fp) / n1);  // rows per matrix, padding included
+    dim3 g13(rows1 / 32, d / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W1, p1, d, ffn, d, rows1, es, e1,
+                       W3 ? 1 : 0, 0);
     int rc = check_launch();
     if (rc != MOE_OK) return rc;
     if (W3) {
-        hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p1, d, ffn, d, fp, es,
-                           2 * ep, 1, 1);
+        hipLaunchKernelGGL(pack_transpose_kernel, g13, dim3(256), 0, st, (const bf16_t*)W3, p1, d, ffn, d, rows1, es,
+                           e1, 1, 1);
         if ((rc = check_launch()) != MOE_OK) return rc;
     }
-    // W2: in[k = ffn][n = d] -> out[n = d][k = fp], zero for k >= ffn
-    dim3 g2(d / 32, fp / 32, E);
-    hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, fp, d, es, ep, 0,
-                       0);
+    // W2: in[k = ffn][n = d] -> packed [n = d][k = fp], zero for k >= ffn and rows n >= d
+    const int rows2 = (int)packed_rows((size_t)d);
+    dim3 g2(rows2 / 32, fp / 32, E);
+    hipLaunchKernelGGL(pack_transpose_kernel, g2, dim3(256), 0, st, (const bf16_t*)W2, p2, ffn, d, fp, rows2, es, e2,
+                       0, 0);
     return check_launch();
 }
 }  // namespace moegps
@@ -1317,8 +1338,11 @@ extern "C" int moe_pack_weights(const void* W1, const void* W3, const void* W2, 
 }
 
 extern "C" size_t moe_packed_weights_relu_bytes(int E, int d, int ffn, int dtype) {
-    if (E < 1 || E > MOE_MAX_EXPERTS || !moegps::ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
-    return (size_t)2 * E * d * moegps::padded_ffn(ffn, dtype) * moegps::dtype_size(dtype);
+    using namespace moegps;
+    if (E < 1 || E > MOE_MAX_EXPERTS || !ffn_shape_in_range(0, d, ffn, 1, dtype)) return 0;
+    if (dtype != MOE_DTYPE_BF16) return (size_t)2 * E * d * ffn * dtype_size(dtype);
+    const int fp = padded_ffn(ffn, dtype);
+    return (size_t)E * (packed_elems1(1, d, fp) + packed_elems2(d, fp)) * sizeof(bf16_t);
 }
 
 extern "C" int moe_pack_weights_relu(const void* W1, const void* W2, int dtype, int E, int d, int ffn, void* packed,
@@ -1437,14 +1461,14 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     const MTile* tiles2 = own2 ? ws.tiles2 : ws.tiles1;
     const int32_t* count2 = own2 ? ws.counts + kCntStride : ws.counts;
     const bf16_t* p13 = (const bf16_t*)packed;
-    const bf16_t* p2 = p13 + (size_t)n1 * E * d * fp;
+    const bf16_t* p2 = p13 + (size_t)E * packed_elems1(n1, d, fp);
     if (timed) (void)hipEventRecord(g_time_events[0], st);
-    rc = launch_gemm_bf16(g1, (const bf16_t*)x_in, d, p13, (size_t)n1 * d * fp, (bf16_t*)ws.h, fp, ws.tiles1,
+    rc = launch_gemm_bf16(g1, (const bf16_t*)x_in, d, p13, packed_elems1(n1, d, fp), (bf16_t*)ws.h, fp, ws.tiles1,
                           ws.counts, ws.queues, n1 * fp, d, group_for(n1 * fp, g1.bn, A * (int64_t)d * 2), rm1, nullptr, st);
     if (timed) (void)hipEventRecord(g_time_events[1], st);
     if (rc != MOE_OK) return rc;
     if (timed) (void)hipEventRecord(g_time_events[2], st);
-    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, fp, p2, (size_t)d * fp, (bf16_t*)y_perm, d, tiles2, count2,
+    rc = launch_gemm_bf16(g2, (const bf16_t*)ws.h, fp, p2, packed_elems2(d, fp), (bf16_t*)y_perm, d, tiles2, count2,
                           ws.queues + 8, d, fp, group_for(d, g2.bn, A * (int64_t)fp * 2), rm2, ws.partials, st);
     if (rc == MOE_OK && split) {
         hipLaunchKernelGGL(add_partials_kernel, dim3(ws.split_capacity < 64 ? ws.split_capacity : 64, 32), dim3(256),
