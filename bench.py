@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "f50ed2c00a6685bcb0827e9601284b52bae65a09652442a6b08f729a97fa3f15",
-                          "fetch_bytes": 6020069243, "write_bytes": 235060250,
+    "cfg2_mixtral_dist": {"source_sha256": "5b796eb74a715907c160a381a4ab2918a4c76dc8a89c2bb64d9064878cbc291b",
+                          "fetch_bytes": 5025256352, "write_bytes": 235021573,
                           "profile": "profiles/gemm1_cfg2_mixtral_traffic_counters.md"},
 }
 
