@@ -335,6 +335,26 @@ def test_ffn_many_tiny_segments():
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
 
 
+@pytest.mark.parametrize("split", [-1, 1])
+def test_ffn_many_experts_full_and_ragged_tiles(split, ffn_options):
+    """1024 experts (the limit) over 2048 segments, a few experts with several full-height tiles and
+    several segments, the rest slivers: every expert's ragged tile has to find its place among a
+    thousand others, with and without tiles split along K."""
+    ffn_options(split=split)
+    rng = np.random.default_rng(18)
+    E, d, ffn, nseg = 1024, 64, 256, 2048
+    cfg = wl.MoEConfig("many", T=1, d=d, ffn=ffn, E=E, k=1, G=256, S=8, dtype="bf16", mode=0, seed=24)
+    seg_sizes = rng.integers(0, 4, size=nseg)
+    slot_expert = rng.integers(0, E, size=nseg)
+    big = rng.choice(nseg, size=12, replace=False)
+    seg_sizes[big] = rng.integers(200, 700, size=12)
+    slot_expert[big] = rng.integers(0, 5, size=12)          # several segments of the same few experts
+    slot_expert = [int(e) if n > 0 or rng.random() < 0.5 else -1 for e, n in zip(slot_expert, seg_sizes)]
+    got, ref, so = run_ffn_case(cfg, [int(n) for n in seg_sizes], slot_expert, seed=19)
+    scale = np.max(np.abs(ref))
+    assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
+
+
 def test_ffn_one_huge_segment_and_empty_rest():
     """All rows in the last of 12 segments: 20 full-height tiles of one expert, nothing else."""
     cfg = wl.MoEConfig("huge", T=1, d=128, ffn=256, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
