@@ -241,7 +241,7 @@ int moe_grouped_ffn_gather(const void* x, int dtype, int T, int k, const int32_t
  * Overrides of the automatic choices inside the grouped FFN, for tests and experiments
  * (process-wide; set them before sizing a workspace, the split option changes its size):
  *   MOE_FFN_OPT_TILE1 / TILE2  tile shape of the first / second product: -1 automatic,
- *                              0 = 256x256x64, 1 = 128x256x64
+ *                              0 = 256x256x64, 1 = 128x256x64, 2 = 32x256x64
  *   MOE_FFN_OPT_SPLIT_K        closing tiles of the second product as parts of K:
  *                              -1 automatic, 0 never, 1 whenever the shapes allow
  *   MOE_FFN_OPT_GROUP_N        N-tiles walked side by side under one run of M-tiles, 0 automatic

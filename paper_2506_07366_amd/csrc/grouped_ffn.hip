@@ -544,11 +544,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
     constexpr int CPR = BK / 8;                 // 16-byte pieces per tile row
     constexpr int IA = BM * CPR / 64;           // wave-wide load instructions per A tile
     constexpr int IB = BN * CPR / 64;
-    constexpr int IAW = IA / NW, IBW = IB / NW;  // per wavefront
+    // per wavefront.  A tile of few rows has fewer activation loads than the workgroup has
+    // wavefronts; the upper wavefronts then repeat the lower ones' loads (same pieces to the
+    // same place), so that every wavefront counts the same number of loads per k-tile.
+    constexpr bool A_SHARED = IA < NW;
+    constexpr int IAW = A_SHARED ? 1 : IA / NW, IBW = IB / NW;
     constexpr int LPT = IAW + IBW;              // loads per thread per k-tile
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int TM16 = WTM / 16, TN16 = WTN / 16;
-    static_assert(IA % NW == 0 && IB % NW == 0, "tile loads must divide over the wavefronts");
+    static_assert((A_SHARED ? NW % IA == 0 : IA % NW == 0) && IB % NW == 0, "tile loads must divide over the wavefronts");
     static_assert(WTM % 16 == 0 && WTN % 16 == 0, "wave tile is a grid of 16x16 MFMA tiles");
     static_assert(!SWIGLU || (WTN % 64 == 0), "gate/up pairs must sit in one wavefront");
     static_assert(LPT * NSTAGE < 64, "vmcnt range");
@@ -680,9 +684,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // stored as it sits in LDS: load i of the wavefront takes its 1 KiB of it as it comes.
         unsigned offA_b[IAW], offB_b[IBW];
         const int lane_p = opaque(lane);
+        const int wave_a = A_SHARED ? wave % IA : wave;
 #pragma unroll
         for (int i = 0; i < IAW; ++i) {
-            const int p = (wave + i * NW) * 64 + lane_p;
+            const int p = (wave_a + i * NW) * 64 + lane_p;
             const int row = p / CPR, slot = p % CPR;
             int r = row < mt.rows ? row : mt.rows - 1;
             if (rm.a_rows) {
@@ -697,13 +702,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // load l of this wavefront's LPT loads of k-tile kt (activations first), one instruction
         const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
         const unsigned lds_wave = lds_base + (unsigned)wave * 1024u;
+        const unsigned lds_wave_a = lds_base + (unsigned)wave_a * 1024u;
         auto issue_load_n = [&](auto L, int kt, int stage) {
             constexpr int l = decltype(L)::value;
             const unsigned sA = lds_wave + (unsigned)(stage * STAGE_BYTES);
             if constexpr (l < IAW) {
                 const unsigned char* base = (const unsigned char*)Ab + (size_t)(kt * (BK * 2));
                 if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
-                    global_to_lds_b128(base, offA_b[l], sA + (unsigned)(l * NW * 1024));
+                    global_to_lds_b128(base, offA_b[l], lds_wave_a + (unsigned)(stage * STAGE_BYTES + l * NW * 1024));
             } else {
                 const unsigned char* base = (const unsigned char*)Bb + (size_t)kt * B_BYTES;
                 global_to_lds_b128(base, offB_b[l - IAW], sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
@@ -1097,7 +1103,7 @@ struct FfnWs {
     int split_all;      // every tile is split (tests)
 };
 
-constexpr int kMinBM = 64;
+constexpr int kMinBM = 32;  // the lowest tile shape
 
 // Process-wide overrides of the automatic choices (moe_grouped_ffn_set_option); -1 / 0 = automatic.
 static std::atomic<int> g_opt_tile1{-1}, g_opt_tile2{-1}, g_opt_split{-1}, g_opt_group_n{0};
@@ -1141,7 +1147,7 @@ static void split_plan(int64_t A, int d, int ffn, int nseg, int dtype, int* spli
         if (kt < 2) return;
         *parts = kt >= kMaxParts ? kMaxParts : 2;
         *split_all = 1;
-        *split_capacity = (int)all_mtiles;
+        *split_capacity = (int)(ceil_div64(A, kMinBM) + (A < nseg ? A : nseg));  // every M-tile of any shape
         return;
     }
     if (kt < 4 * kMaxParts) return;
@@ -1204,14 +1210,19 @@ static GemmVariant make_variant() {
 }
 
 // Tile shapes built into the library: 0 = 256x256x64 with two LDS stages, 1 = 128x256x64 with
-// three (for products with too few 256-row tiles to fill the chip twice, and for slivers).
-constexpr int kNumVariants = 2;
+// three (for products with too few 256-row tiles to fill the chip twice), 2 = 32x256x64 with
+// four (for slivers of a few rows per expert, where the product only streams weights: three
+// k-tiles of a weight panel in flight per workgroup instead of two).
+constexpr int kNumVariants = 3;
 static const GemmVariant kGemmSwiglu[kNumVariants] = {make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu>(),
-                                                      make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>()};
+                                                      make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>(),
+                                                      make_variant<32, 256, 64, 2, 4, 4, kEpiSwiglu>()};
 static const GemmVariant kGemmRelu[kNumVariants] = {make_variant<256, 256, 64, 2, 4, 2, kEpiRelu>(),
-                                                    make_variant<128, 256, 64, 2, 4, 3, kEpiRelu>()};
+                                                    make_variant<128, 256, 64, 2, 4, 3, kEpiRelu>(),
+                                                    make_variant<32, 256, 64, 2, 4, 4, kEpiRelu>()};
 static const GemmVariant kGemmPlain[kNumVariants] = {make_variant<256, 256, 64, 2, 4, 2, kEpiNone>(),
-                                                     make_variant<128, 256, 64, 2, 4, 3, kEpiNone>()};
+                                                     make_variant<128, 256, 64, 2, 4, 3, kEpiNone>(),
+                                                     make_variant<32, 256, 64, 2, 4, 4, kEpiNone>()};
 
 // timing hook: events recorded around the two products of the next call on this thread
 static thread_local hipEvent_t g_time_events[4];
@@ -1418,17 +1429,23 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     // Tile shape per product: 256x256 unless the product has too few such tiles to keep 256
     // workgroups busy for two rounds, or the segments are slivers of a few rows each
     // (decode), then 128x256 with three stages.  The tile count is only known on the device;
-    // the host estimates it from the row count.
-    auto pick = [&](int forced, int n_cols) {
+    // the host estimates it from the row count.  A product of slivers with few k-tiles per tile
+    // (the second product at the hidden widths of fine-grained experts) takes 32x256 with four
+    // stages: the pipeline's fill and drain are a larger share of such a tile, and the deeper
+    // prefetch pays (decode at 128 experts, 24 k-tiles: 0.201 -> 0.192 ms); on long tiles it
+    // does not make up for the extra M-tiles of experts with more than 32 rows (same batch,
+    // first product, 64 k-tiles: 0.369 -> 0.392 ms).
+    auto pick = [&](int forced, int n_cols, int k_tiles) {
         if (forced >= 0) return forced;
+        if (A < (int64_t)16 * nrange && k_tiles <= 32) return 2;
         if (A < (int64_t)64 * nrange) return 1;
         const int64_t est_mtiles = A / 256 + (nrange + 1) / 2;
         return est_mtiles * ceil_div(n_cols, 256) > 2 * kGemmGrid ? 0 : 1;
     };
     const int fp = padded_ffn(ffn, dtype);  // hidden width the kernels see
     const int n1 = relu ? 1 : 2;            // matrices in the first product
-    const int v1 = pick(g_opt_tile1.load(), n1 * fp);
-    const int v2 = pick(g_opt_tile2.load(), d);
+    const int v1 = pick(g_opt_tile1.load(), n1 * fp, d / 64);
+    const int v2 = pick(g_opt_tile2.load(), d, fp / 64);
     // N-tiles walked side by side under one run of M-tiles.  A run of 32 tiles is 32/g M-tiles
     // under g weight panels; every group streams the activation rows again.  Up to 12 N-tiles
     // are walked together, so the rows are read once.  Wider outputs are walked in groups: of 4

@@ -366,8 +366,8 @@ def test_ffn_one_huge_segment_and_empty_rest():
 
 
 @pytest.mark.parametrize("split", [0, 1])
-@pytest.mark.parametrize("tile2", [0, 1])
-@pytest.mark.parametrize("tile1", [0, 1])
+@pytest.mark.parametrize("tile2", [0, 1, 2])
+@pytest.mark.parametrize("tile1", [0, 1, 2])
 def test_ffn_every_tile_variant(tile1, tile2, split, ffn_options):
     """The tile shapes built into the library (forced through moe_grouped_ffn_set_option) all
     compute the same FFN, with the closing tiles of the second product computed whole (0) or as
@@ -377,7 +377,7 @@ def test_ffn_every_tile_variant(tile1, tile2, split, ffn_options):
     cfg = wl.MoEConfig("v", T=1, d=256, ffn=320, E=5, k=1, G=4, S=3, dtype="bf16", mode=0, seed=21)
     seg_sizes = [1, 0, 127, 129, 0, 256, 257, 63, 300, 0, 5, 64]
     slot_expert = [0, 1, 2, 3, -1, 4, 0, 1, 2, 3, 4, 0]
-    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=tile1 * 2 + tile2)
+    got, ref, so = run_ffn_case(cfg, seg_sizes, slot_expert, seed=tile1 * 3 + tile2)
     scale = np.max(np.abs(ref))
     assert np.all(np.max(np.abs(got - ref), axis=1) <= TOL["bf16"] * scale)
 

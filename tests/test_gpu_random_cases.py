@@ -45,8 +45,8 @@ def test_random_ffn_cases(seed):
             b0 = int(rng.integers(0, nseg))
             b1 = int(rng.integers(b0, nseg + 1))
         # any tile shape for either product, the second product whole, by the rule or split everywhere
-        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE1, int(rng.integers(-1, 2)))
-        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE2, int(rng.integers(-1, 2)))
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE1, int(rng.integers(-1, 3)))
+        B.moe_grouped_ffn_set_option(B.FFN_OPT_TILE2, int(rng.integers(-1, 3)))
         B.moe_grouped_ffn_set_option(B.FFN_OPT_SPLIT_K, int(rng.integers(-1, 2)))
         try:
             ref = grouped_ffn(x, so, slot_expert, W1, None if relu else W3, W2, b0, b1)
