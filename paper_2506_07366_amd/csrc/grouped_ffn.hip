@@ -681,8 +681,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
         // zero rows of the packed form; their products are computed and dropped in the
         // epilogue).  (uniform base) + (32-bit lane offset) is an addressing mode of the load
         // instruction, so the loads spend no vector ALU work on addresses.  A weight tile is
-        // stored as it sits in LDS: load i of the wavefront takes its 1 KiB of it as it comes.
-        unsigned offA_b[IAW], offB_b[IBW];
+        // stored as it sits in LDS: load i of the wavefront takes its 1 KiB of it as it comes, so
+        // one lane offset serves all of them and the rest of the address is uniform.  Whether
+        // that offset is kept in a register or worked out at each load (one instruction) decides,
+        // at the 256 registers of the tallest shape, which of the three epilogues the compiler
+        // fits without scratch memory: the form below keeps all of them at none.
+        constexpr bool KEEP_OFFB = SWIGLU;
+        unsigned offA_b[IAW];
+        unsigned offB_kept[KEEP_OFFB ? IBW : 1];
         const int lane_p = opaque(lane);
         const int wave_a = A_SHARED ? wave % IA : wave;
 #pragma unroll
@@ -696,8 +702,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
             }
             offA_b[i] = ((unsigned)r * (unsigned)lda + (unsigned)((slot ^ swz(row)) * 8)) * 2u;
         }
+        if constexpr (KEEP_OFFB) {
 #pragma unroll
-        for (int i = 0; i < IBW; ++i) offB_b[i] = (unsigned)(((wave + i * NW) * 64 + lane_p) * 16);
+            for (int i = 0; i < IBW; ++i) offB_kept[i] = (unsigned)(((wave + i * NW) * 64 + lane_p) * 16);
+        }
+
 
         // load l of this wavefront's LPT loads of k-tile kt (activations first), one instruction
         const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -711,8 +720,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_kernel(
                 if (!SKIP_TAIL_LOADS || (wave + l * NW) * ROWS_PER_LOAD < mt.rows)
                     global_to_lds_b128(base, offA_b[l], lds_wave_a + (unsigned)(stage * STAGE_BYTES + l * NW * 1024));
             } else {
-                const unsigned char* base = (const unsigned char*)Bb + (size_t)kt * B_BYTES;
-                global_to_lds_b128(base, offB_b[l - IAW], sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
+                if constexpr (KEEP_OFFB) {
+                    const unsigned char* base = (const unsigned char*)Bb + (size_t)kt * B_BYTES;
+                    global_to_lds_b128(base, offB_kept[l - IAW], sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
+                } else {
+                    const unsigned char* base =
+                        (const unsigned char*)Bb + ((size_t)kt * B_BYTES + (l - IAW) * NW * 1024);
+                    global_to_lds_b128(base, (unsigned)((wave * 64 + opaque(lane)) * 16),
+                                       sA + (unsigned)(A_BYTES + (l - IAW) * NW * 1024));
+                }
             }
         };
         auto issue_loads = [&](int kt, int stage) {
@@ -1212,7 +1228,8 @@ static GemmVariant make_variant() {
 // Tile shapes built into the library: 0 = 256x256x64 with two LDS stages, 1 = 128x256x64 with
 // three (for products with too few 256-row tiles to fill the chip twice), 2 = 32x256x64 with
 // four (for slivers of a few rows per expert, where the product only streams weights: three
-// k-tiles of a weight panel in flight per workgroup instead of two).
+// k-tiles of a weight panel in flight per workgroup instead of two, and an eighth of the
+// activation tile to fetch for rows that are not there).
 constexpr int kNumVariants = 3;
 static const GemmVariant kGemmSwiglu[kNumVariants] = {make_variant<256, 256, 64, 2, 4, 2, kEpiSwiglu>(),
                                                       make_variant<128, 256, 64, 2, 4, 3, kEpiSwiglu>(),
@@ -1431,10 +1448,11 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
     // (decode), then 128x256 with three stages.  The tile count is only known on the device;
     // the host estimates it from the row count.  A product of slivers with few k-tiles per tile
     // (the second product at the hidden widths of fine-grained experts) takes 32x256 with four
-    // stages: the pipeline's fill and drain are a larger share of such a tile, and the deeper
-    // prefetch pays (decode at 128 experts, 24 k-tiles: 0.201 -> 0.192 ms); on long tiles it
-    // does not make up for the extra M-tiles of experts with more than 32 rows (same batch,
-    // first product, 64 k-tiles: 0.369 -> 0.392 ms).
+    // stages: the taller shapes fetch their whole activation tile every k-tile, rows that are
+    // not there as copies of the last one, half as many bytes again as the weights at 128 rows
+    // (decode at 128 experts, 24 k-tiles: 0.201 -> 0.192 ms; 64x256 with four stages stays at
+    // 0.200); on long tiles that does not make up for the extra M-tiles of experts with more
+    // than 32 rows (same batch, first product, 64 k-tiles: 0.369 -> 0.392 ms).
     auto pick = [&](int forced, int n_cols, int k_tiles) {
         if (forced >= 0) return forced;
         if (A < (int64_t)16 * nrange && k_tiles <= 32) return 2;
