@@ -164,7 +164,9 @@ def test_plan_many_ranks():
                                        # both sides of the one-workgroup path's limits: 8192 assignments,
                                        # 512 experts, 512 segments
                                        (400, 512, 8, 64, 8), (400, 513, 8, 64, 9), (1024, 300, 8, 32, 16),
-                                       (1024, 300, 8, 33, 16), (1, 1, 1, 1, 1), (8192, 512, 1, 128, 4)])
+                                       (1024, 300, 8, 33, 16), (1, 1, 1, 1, 1), (8192, 512, 1, 128, 4),
+                                       # hundreds of chunks; many chunks at the largest expert and segment counts
+                                       (70000, 16, 8, 4, 5), (20000, 1024, 16, 256, 8)])
 def test_permute_small(mode, T, E, k, G, S):
     cfg = wl.MoEConfig("p", T=T, d=16, ffn=8, E=E, k=k, G=G, S=S, dtype="f32", mode=mode, alpha=0.3,
                        sigma_pred=0.3, acc=0.8, seed=T + E)
