@@ -92,6 +92,6 @@ def test_ffn_workspace_size_rule():
         assert opt(SPLIT, 1) == 0
         assert ws(1024, 512, 1024, 12, 1) > ws(1024, 512, 64, 12, 1)  # forced, but not with a single k-tile
         assert ws(-1, 64, 64, 1, 1) == 0 and ws(16, 64, 64, 0, 1) == 0
-        assert opt(SPLIT, 2) == -1 and opt(99, 0) == -1 and opt(binding.FFN_OPT_TILE1, 2) == -1
+        assert opt(SPLIT, 2) == -1 and opt(99, 0) == -1 and opt(binding.FFN_OPT_TILE1, 3) == -1
     finally:
         opt(SPLIT, -1)
