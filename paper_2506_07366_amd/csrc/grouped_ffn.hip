@@ -1457,12 +1457,18 @@ static int grouped_ffn_impl(int relu, const void* x_in, int64_t rows_in, const i
         if (forced >= 0) return forced;
         if (A < (int64_t)16 * nrange && k_tiles <= 32) return 2;
         if (A < (int64_t)64 * nrange) return 1;
-        // fewer than 192 rows per expert on average: most 256-row tiles would be less than half
-        // full (128 experts, 16384 rows: 623 against 683 us for the first product; at 32768 rows
-        // the tall shape is ahead again, 915 against 955 us)
-        if (A < (int64_t)192 * (E < nrange ? E : nrange)) return 1;
-        const int64_t est_mtiles = A / 256 + (nrange + 1) / 2;
-        return est_mtiles * ceil_div(n_cols, 256) > 2 * kGemmGrid ? 0 : 1;
+        // fewer than 256 rows per expert on average: most 256-row tiles would be ragged (128
+        // experts, 16384 rows: 623 against 683 us for the first product; 64 experts, 12288 rows:
+        // 226 against 258 us; at 256 rows per expert the shapes are within 4 % of each other, at
+        // 384 equal)
+        const int64_t experts = E < nrange ? E : nrange;
+        if (A < 256 * experts) return 1;
+        // few tiles: the 128-row shape fills the chip better, unless the experts are large
+        // enough for whole 256-row tiles and those still make more than one round (8 experts,
+        // 4096 rows, second product: 476 against 521 us)
+        const int64_t est_tiles = (A / 256 + (nrange + 1) / 2) * ceil_div(n_cols, 256);
+        if (A >= 512 * experts) return est_tiles > kGemmGrid ? 0 : 1;
+        return est_tiles > 2 * kGemmGrid ? 0 : 1;
     };
     const int fp = padded_ffn(ffn, dtype);  // hidden width the kernels see
     const int n1 = relu ? 1 : 2;            // matrices in the first product
