@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "f0ad1450fce865c123e068048224ffde3d6f1f3bc01b8618fe171c31b5e5c96f",
-                          "fetch_bytes": 5183525552, "write_bytes": 235022182,
+    "cfg2_mixtral_dist": {"source_sha256": "e96dc83088274b3cbbbfe8e57b594d4ee439c5ea4ba69b937dce54c23867ae74",
+                          "fetch_bytes": 5053662016, "write_bytes": 235021670,
                           "profile": "profiles/gemm1_cfg2_mixtral_traffic_counters.md"},
 }
 
