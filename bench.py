@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_07366_amd", "csrc",
                              "grouped_ffn.hip")
 TRAFFIC = {
-    "cfg2_mixtral_dist": {"source_sha256": "e96dc83088274b3cbbbfe8e57b594d4ee439c5ea4ba69b937dce54c23867ae74",
-                          "fetch_bytes": 5053662016, "write_bytes": 235021670,
+    "cfg2_mixtral_dist": {"source_sha256": "740699f2e08462455696c06cccf4e9c8c48cd40a0bbfb49dd36673e836e30972",
+                          "fetch_bytes": 5228558792, "write_bytes": 235022779,
                           "profile": "profiles/gemm1_cfg2_mixtral_traffic_counters.md"},
 }
 
