@@ -167,6 +167,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2_mixtral_dist")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="run the config's shape at another batch size (the tables of batch sizes in DESIGN.md); "
+                         "the config's own size when 0")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also print per-stage timings to stderr")
     ap.add_argument("--fused-gather", action="store_true",
@@ -199,6 +202,8 @@ def main():
     B.load_library()   # fails loudly if the HIP library is missing
 
     cfg = wl.CONFIGS[args.config]
+    if args.tokens > 0 and args.tokens != cfg.T:
+        cfg = cfg.replace(T=args.tokens, name=f"{cfg.name}@T={args.tokens}")   # (no stored counter figures for it)
     torch.cuda.set_device(0)
     if args.copy_calibration:
         # fp32 "packing" is three launches of copy_u4_kernel, each reading and writing E*d*ffn*4 bytes
@@ -267,7 +272,7 @@ def main():
 
     flops1 = (2.0 if cfg.act == "relu" else 4.0) * cfg.A * cfg.d * cfg.ffn   # gate + up products (ReLU form: one)
     flops2 = 2.0 * cfg.A * cfg.d * cfg.ffn      # down product
-    traffic, traffic_source = measured_traffic(args.config)
+    traffic, traffic_source = measured_traffic(cfg.name)
     if bf16:
         g1_ms = float(np.mean([q[0].elapsed_time(q[1]) for q in evs]))
         g2_ms = float(np.mean([q[2].elapsed_time(q[3]) for q in evs]))
